@@ -1,0 +1,24 @@
+"""Plain CPU oracle for batched group rollout generation with Pilot-Commit
+allocation.
+
+TEST INFRASTRUCTURE ONLY.  This package is the slow, obviously-correct
+reference the HIP library is checked against.  It shares no code with the
+library, never imports it, and nothing on the product path may import it:
+only the tests, the smoke check and the benchmark's CPU-baseline leg do.
+
+Modules
+  philox      Philox4x32-10 counter-based generator (Salmon et al., SC'11)
+  decoder     pre-norm GQA decoder forward: brute force and KV-cached
+  sampler     temperature softmax + inverse-CDF sampling (Section 3.1 sampling)
+  allocation  group statistics (Eq. 3), pilot filter / eviction / commit set
+              (Section 3.3, Algorithm 1), group-relative advantages, sampling
+              cost (Section 4.3)
+  rewards     the synthetic binary reward rules of the workloads
+  rollout     pilot pass -> select -> commit pass -> advantages, end to end
+
+Pin status: every function here is pinned by tests/test_oracle_*.py against
+closed forms, published known-answer vectors, invariants, brute force or an
+independent library routine, except the end-to-end token sequences of
+rollout.pilot_commit_step, for which no published values exist:
+"parity unpinned" for those (their parts are each pinned).
+"""
