@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark: generated rollout tokens/s of one full Pilot-Commit sampling
+step (shared-prefix prefill, pilot rollouts, group statistics, selection,
+commit rollouts on the kept prompts, advantages) at the 1.5B shape on ONE
+MI355X, with the decode-attention kernel priced against the HBM roofline and
+the CPU oracle timed beside it on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints one JSON line.  A "step" is one pass of the whole path over one batch
+of synthetic prompts (64 prompts x 256 tokens, pilot 4 + commit 4 rollouts,
+1024 new tokens each).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
+
+
+def decode_bytes_per_step(model, n_prompts_active, prompt_len, n_seqs, t):
+    """Algorithmic HBM bytes of decode step t (the step that feeds generated token t-1):
+    all weights once + prefix KV once per prompt + generated KV per sequence (the appended
+    token included).  Logit traffic is excluded."""
+    w = (model.body_params() + model.lm_head_params()) * model.elem_bytes()
+    kv = (n_prompts_active * prompt_len + n_seqs * t) * model.kv_bytes_per_token()
+    return w + kv
+
+
+def attention_bytes_per_launch(model, n_prompts_active, prompt_len, n_seqs, t):
+    """Algorithmic bytes of ONE decode-attention launch (one layer) at step t."""
+    per_tok = 2 * model.n_kv_heads * model.head_dim * model.elem_bytes()
+    return (n_prompts_active * prompt_len + n_seqs * t) * per_tok
+
+
+def cpu_baseline(wl, w_dev, prompts, uids, seed):
+    """Times the oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    import torch
+    from oracle import rollout as orollout
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads()])
+    except Exception:
+        threads = torch.get_num_threads()
+    w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w_dev.items()}
+    n_roll, n_new = 2, 4
+    t0 = time.perf_counter()
+    toks, lens, _, _ = orollout.generate_group(wl.model, w_cpu, prompts[0], int(uids[0]), range(n_roll), n_new,
+                                               wl.temperature, seed)
+    dt = time.perf_counter() - t0
+    return {"value": float(lens.sum()) / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": "1 prompt x %d tokens prefilled once, %d rollouts x %d new tokens, float64 numpy (%.1f s)"
+                      % (wl.prompt_len, n_roll, n_new, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=1)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--time-every", type=int, default=64)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported (no multi-GPU path "
+                         "exists in this library)\n" % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads
+    import paper_2605_26606_amd as pc
+
+    wl = workloads.WORKLOADS[args.workload]
+    if args.new_tokens:
+        wl = workloads.scaled(wl, new_tokens=args.new_tokens)
+    m = wl.model
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w = workloads.make_weights(m, wl.seed_weights, device=dev)
+    prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, m.vocab, wl.seed_prompts)
+    uids = workloads.make_prompt_uids(wl.n_prompts)
+    P, Lp, T = wl.n_prompts, wl.prompt_len, wl.new_tokens
+    n_max = P * max(wl.n_pilot, wl.n_commit)
+    kv_tokens = P * Lp + n_max * (T + 64) + 4096
+    ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
+                     max_slots=P + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    toks = torch.from_numpy(prompts.reshape(-1).astype(np.int32)).to(dev)
+    eos_id = workloads.make_eos_id(m.vocab, wl.seed_eos) if wl.eos else -1
+    p_q = workloads.make_success_probs(P, wl.seed_reward) if wl.reward == "bernoulli" else None
+    ru = workloads.make_reward_uniforms(P, wl.n_pilot + wl.n_commit, wl.seed_reward) \
+        if wl.reward == "bernoulli" else None
+    stream = torch.cuda.Stream()
+
+    def one_step(seed, timed_steps=None, timings=None):
+        with torch.cuda.stream(stream):
+            return pc.pilot_commit_step(ctx, wl, toks, cu, uids, seed, eos_id, 0.0, p_q, ru,
+                                        time_class=pc.PC_KERNEL_ATTN_DECODE if timed_steps is not None else -1,
+                                        time_every=args.time_every if timed_steps is not None else 0,
+                                        timed_steps=timed_steps, timings=timings)
+
+    for i in range(args.warmup):
+        one_step(wl.seed_sampler + 1000 + i)
+    torch.cuda.synchronize()
+    pc.pc_timing_read(ctx, reset=True)
+
+    timed_steps, timings, outs = [], [], []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        tm = {}
+        outs.append(one_step(wl.seed_sampler + i, timed_steps, tm))
+        timings.append(tm)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    tokens = sum(o["tokens_generated"] for o in outs)
+    attn_ms, attn_launches = pc.pc_timing_read(ctx, reset=True)
+    # algorithmic bytes of the timed attention launches (every layer of every timed step)
+    attn_bytes = sum(attention_bytes_per_launch(m, pa, Lp, n, t) for (_, t, n, pa) in timed_steps) * m.n_layers
+    roof = None
+    if attn_launches > 0 and attn_ms > 0:
+        avg_ms = attn_ms / attn_launches
+        achieved = attn_bytes / attn_launches / (avg_ms * 1e-3) / 1e9
+        roof = {"kernel": "attention_decode_mfma_kernel", "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_us": round(avg_ms * 1e3, 2), "launches_timed": int(attn_launches),
+                "bytes_per_launch": int(attn_bytes / attn_launches)}
+    # whole decode loop against the HBM roofline (weights + KV per step, prefix counted once per prompt)
+    dec_bytes = dec_ms = 0.0
+    for o, tm in zip(outs, timings):
+        K = int(o["counts"][0])
+        for t in range(1, T):
+            dec_bytes += decode_bytes_per_step(m, P, Lp, P * wl.n_pilot, t)
+            if K:
+                dec_bytes += decode_bytes_per_step(m, K, Lp, K * wl.n_commit, t)
+        dec_ms += tm.get("pilot_ms", 0.0) + tm.get("commit_ms", 0.0)
+    prefill_flops = 2.0 * m.body_params() * P * Lp + 2.0 * m.lm_head_params() * P \
+        + 2.0 * m.n_layers * P * m.n_q_heads * m.head_dim * Lp * Lp
+    prefill_ms = sum(tm.get("prefill_ms", 0.0) for tm in timings) / max(1, len(timings))
+    result = {
+        "metric": "rollout tokens/s on 1 MI355X (1.5B shape, G=8); decode HBM GB/s % of peak",
+        "value": round(tokens / dt, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(dt * 1e3 / max(1, args.steps), 2), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
+        "config": {"workload": "%s: %d prompts x %d tokens, pilot %d + commit %d rollouts on kept prompts, %d new "
+                               "tokens, L%d d%d %dq/%dkv hd%d ff%d V%d, random init" %
+                               (wl.name, P, Lp, wl.n_pilot, wl.n_commit, T, m.n_layers, m.d_model, m.n_q_heads,
+                                m.n_kv_heads, m.head_dim, m.d_ff, m.vocab),
+                   "kept_prompts": [int(o["counts"][0]) for o in outs],
+                   "rollouts": [int(o["rollouts"]) for o in outs]},
+        "roofline": roof,
+        "decode": {"ms": round(dec_ms, 1), "steps": sum(o["decode_steps"] for o in outs),
+                   "algorithmic_GBps": round(dec_bytes / max(dec_ms, 1e-9) / 1e6, 1),
+                   "frac_hbm": round(dec_bytes / max(dec_ms, 1e-9) / 1e6 / HBM_PEAK_GBPS, 4)},
+        "prefill": {"ms": round(prefill_ms, 2), "TFLOPs": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9, 1),
+                    "frac_mfma": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, w, prompts, uids, wl.seed_sampler)
+    ctx.close()
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,210 @@
+/*
+ * pc.h -- C ABI of the group-rollout library for AMD MI355X (gfx950).
+ *
+ * The library generates the rollouts that a Pilot-Commit training step
+ * consumes: for a batch of prompts it samples a few "pilot" completions per
+ * prompt from a decoder-only policy, scores each prompt by the mean of its
+ * binary rewards, keeps the prompts whose pilot success rate lies in
+ * [p_lower, p_upper], samples further "commit" completions for the kept
+ * prompts only, and returns group-relative advantages over the union
+ * (paper Section 3.1, Section 3.3, Algorithm 1).
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary host memory.  Every pointer below says which.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise the stream unless the
+ *     comment of the call says so.  The caller orders calls on one stream.
+ *   - Every call returns a pc_status: PC_OK (0) or a negative error code.  On
+ *     error nothing has been launched and no library state has changed;
+ *     pc_last_error() returns a message for the calling thread's last error.
+ *   - The library never throws and never aborts.
+ *   - All matrices are row-major [out_features, in_features].
+ */
+#ifndef PC_H
+#define PC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t pc_status;
+#define PC_OK 0
+#define PC_ERR_INVALID_ARG (-1)
+#define PC_ERR_OOM (-2)         /* KV pool, slot table or scratch exhausted */
+#define PC_ERR_HIP (-3)         /* a HIP runtime call failed */
+#define PC_ERR_UNSUPPORTED (-4) /* shape outside what the kernels support */
+
+#define PC_DTYPE_F32 0
+#define PC_DTYPE_BF16 1
+
+typedef struct pc_ctx pc_ctx;
+
+/* Shape of the decoder-only policy pi_theta (Section 3.1): pre-norm
+ * transformer, RMSNorm, rotary positions (rotate-half pairing), grouped-query
+ * attention, SwiGLU feed-forward.  dtype is the storage type of the matrices,
+ * embeddings and KV cache; the residual stream, norm statistics, softmax and
+ * logits are always fp32. */
+typedef struct {
+    int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
+    float rms_eps, rope_theta;
+    int32_t dtype; /* PC_DTYPE_F32 or PC_DTYPE_BF16 */
+} pc_model_config;
+
+/* Device pointers to the weights.  The per-layer members are HOST arrays of
+ * n_layers DEVICE pointers.  Norm gains are fp32 [d_model]; everything else
+ * has the model dtype.  lm_head may alias tok_embed (tied embeddings).
+ * pc_create copies the per-layer matrices into its own fused layout, so only
+ * tok_embed, lm_head and final_norm must outlive the context. */
+typedef struct {
+    const void *tok_embed;  /* [vocab, d_model] */
+    const void *lm_head;    /* [vocab, d_model] */
+    const void *final_norm; /* fp32 [d_model] */
+    const void *const *attn_norm; /* fp32 [d_model] each */
+    const void *const *wq;        /* [n_q_heads*head_dim, d_model] */
+    const void *const *wk;        /* [n_kv_heads*head_dim, d_model] */
+    const void *const *wv;        /* [n_kv_heads*head_dim, d_model] */
+    const void *const *wo;        /* [d_model, n_q_heads*head_dim] */
+    const void *const *ffn_norm;  /* fp32 [d_model] each */
+    const void *const *w_gate;    /* [d_ff, d_model] */
+    const void *const *w_up;      /* [d_ff, d_model] */
+    const void *const *w_down;    /* [d_model, d_ff] */
+} pc_weights;
+
+/* Paged KV cache.  The context owns a pool of kv_pool_bytes (rounded down to
+ * whole blocks of block_size tokens across all layers), a table of max_slots
+ * slots (one per live prompt or sequence) and activation scratch for
+ * max_batch_rows rows (the largest number of token rows one call processes:
+ * prompt tokens of one prefill chunk, or sequences of one decode step). */
+typedef struct {
+    int32_t block_size;     /* tokens per KV block; a multiple of 32, at most 256 */
+    int64_t kv_pool_bytes;
+    int32_t max_slots;
+    int32_t max_ctx;        /* longest prompt + completion, in tokens */
+    int32_t max_batch_rows;
+} pc_cache_config;
+
+/* Options for pc_set_option. */
+#define PC_OPT_USE_GRAPH 1   /* 1: replay the decode step as a HIP graph (default 1) */
+#define PC_OPT_FORCE_SIMT 2  /* 1: plain-ALU kernels also for bf16 (debugging aid; default 0) */
+#define PC_OPT_TIME_NEXT_STEP 3 /* value = a PC_KERNEL_* class: the next pc_decode_step runs eagerly (no graph)
+                                   with a HIP event pair around every launch of that class; -1 disarms */
+
+/* Kernel classes of a decode step, for PC_OPT_TIME_NEXT_STEP / pc_timing_read. */
+#define PC_KERNEL_ATTN_DECODE 0
+#define PC_KERNEL_GEMM_QKV 1
+#define PC_KERNEL_GEMM_WO 2
+#define PC_KERNEL_GEMM_GATE_UP 3
+#define PC_KERNEL_GEMM_DOWN 4
+#define PC_KERNEL_GEMM_LM_HEAD 5
+
+const char *pc_last_error(void);
+
+/* Creates a context on the current HIP device.  Allocates the KV pool, slot
+ * tables, scratch and the fused weight copies; synchronises the device once.
+ * `out` (host) receives the context. */
+pc_status pc_create(const pc_model_config *model, const pc_weights *weights,
+                    const pc_cache_config *cache, pc_ctx **out);
+pc_status pc_destroy(pc_ctx *ctx);
+pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value);
+/* Sums the event pairs recorded since the last reset: total_ms (host double) and launches (host
+ * int64) over all timed launches.  SYNCHRONISES on the recorded events.  reset != 0 recycles them. */
+pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, int32_t reset);
+/* Number of free KV blocks / total KV blocks (host bookkeeping, no GPU work). */
+pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks);
+
+/* Shared-prefix prefill: the context pi_theta(. | q) of each prompt is computed
+ * ONCE (Section 3.3: n rollouts o_j ~ pi_theta(.|q) per prompt q); all rollouts
+ * of the prompt later reference the same KV blocks through their block tables.
+ *   prompt_tokens  device int32, prompts packed back to back
+ *   cu_lens        host int32 [P+1], cu_lens[0] = 0, prompt p = tokens[cu_lens[p] .. cu_lens[p+1])
+ *   handle_out     host int32 [P]: a handle per prompt (a slot index)
+ *   last_logits    device fp32 [P, vocab]: next-token logits after each prompt
+ * Token ids outside [0, vocab) are read as id 0.  Prompts are processed in
+ * chunks of at most max_batch_rows tokens; a prompt longer than that, longer
+ * than max_ctx, or empty is PC_ERR_INVALID_ARG; running out of blocks or slots
+ * is PC_ERR_OOM (nothing is kept). */
+pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens,
+                            int32_t P, int32_t *handle_out, float *last_logits, void *stream);
+
+/* Starts one sequence per entry of prompt_handle (host int32 [n]; a handle may
+ * repeat: that is the group of G rollouts of a prompt).  Each sequence's block
+ * table references the prompt's full blocks; a partially filled last prompt
+ * block is copied into a private block.  Blocks for max_new_tokens further
+ * tokens are reserved now, so that decode steps never allocate.
+ *   seq_out  host int32 [n]: sequence ids (slot indices). */
+pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens,
+                  int32_t *seq_out, void *stream);
+
+/* One decode step pi_theta(o_t | q, o_<t) (Section 3.1) for n sequences:
+ * feeds one token per sequence, appends its K/V to the cache, returns the
+ * next-token logits.
+ *   seq        host int32 [n], distinct sequence ids
+ *   tokens_in  device int32 [n]
+ *   logits     device fp32 [n, vocab]
+ * With PC_OPT_USE_GRAPH the step is captured once per (sequence list,
+ * pointers, stream) and replayed; keep the pointers stable across steps.
+ * A sequence that has used up its reserved tokens is PC_ERR_INVALID_ARG. */
+pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n,
+                         float *logits, void *stream);
+
+/* Releases sequences (kind 0) or prompts (kind 1); ids is host int32 [n].
+ * Shared blocks are freed when their last user goes. */
+pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind);
+
+/* Samples one token per row: o_t ~ softmax(logits / temperature)
+ * (Section 3.1 sampling; Section 4.2: temperature 1.0, top_p 1.0), by inverse
+ * CDF with a Philox4x32-10 uniform keyed by (seed; step, sequence uid).
+ *   logits      device fp32 [*, vocab]
+ *   logit_row   device int32 [n] or NULL: row of `logits` that output row i
+ *               reads (NULL: row i).  Lets G rollouts share a prompt's row.
+ *   seq_uid     device uint64 [n]
+ *   step        device int32 [n] or NULL; row i uses step_base + step[i]
+ *   eos_id      -1 = none; eos_logit_bias is added to that id's scaled logit
+ *   tokens_out  device int32 [n]
+ *   logprob_out device fp32 [n] or NULL: log-probability of the sampled token
+ *   finished    device uint8 [n] or NULL, in/out: set when eos_id is sampled;
+ *               a row already finished on entry yields eos_id and logprob 0. */
+pc_status pc_sample(const float *logits, const int32_t *logit_row, int32_t n, int32_t vocab,
+                    float temperature, uint64_t seed, const uint64_t *seq_uid, const int32_t *step,
+                    int32_t step_base, int32_t eos_id, float eos_logit_bias, int32_t *tokens_out,
+                    float *logprob_out, uint8_t *finished, void *stream);
+
+/* Per-prompt reward statistics (Eq. 3; Section 3.3 pilot success rate
+ * p_hat = (1/n) sum r_j, Var = p(1-p) for binary rewards).
+ *   rewards    device fp32 [N]; group_off device int32 [P+1] (ascending offsets)
+ *   n_pos      device int32 [P]: number of non-zero rewards
+ *   n_tot      device int32 [P]: group size
+ *   mean, var  device fp32 [P]: mean and POPULATION variance (divide by the
+ *              group size); 0 for an empty group.  Any output may be NULL. */
+pc_status pc_group_stats(const float *rewards, const int32_t *group_off, int32_t P, int32_t *n_pos,
+                         int32_t *n_tot, float *mean, float *var, void *stream);
+
+/* Pilot filter, eviction flags and the commit set (Section 3.3; Algorithm 1).
+ *   p_hat       device fp32 [P], in batch order
+ *   cls         device uint8 [P]: 0 too hard (p_hat < p_lower), 1 keep,
+ *               2 too easy (p_hat > p_upper)
+ *   evict       device uint8 [P]: p_hat >= p_solve (independent of cls)
+ *   commit_idx  device int32 [P]: the first min(#keep, b_t) kept indices,
+ *               ascending (b_t <= 0: no cap); entries past counts[0] untouched
+ *   surplus_idx device int32 [P]: the remaining kept indices, ascending
+ *   counts      device int32 [4]: n_commit, n_surplus, n_easy, n_hard
+ * cls, evict, surplus_idx may be NULL. */
+pc_status pc_select_commit(const float *p_hat, int32_t P, float p_lower, float p_upper, float p_solve,
+                           int32_t b_t, uint8_t *cls, uint8_t *evict, int32_t *commit_idx,
+                           int32_t *surplus_idx, int32_t *counts, void *stream);
+
+/* Group-relative advantages A_i = (r_i - mu) / (sigma + eps) (Section 3.1,
+ * Eq. 3), one group per kept prompt = its pilot and commit rollouts together
+ * (Section 3.3 "Training").  A reward equal to the group mean gives exactly 0.
+ *   rewards device fp32 [N]; group_off device int32 [P+1]
+ *   adv device fp32 [N]; mu, sigma device fp32 [P] or NULL. */
+pc_status pc_advantages(const float *rewards, const int32_t *group_off, int32_t P, float eps, float *adv,
+                        float *mu, float *sigma, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PC_H */

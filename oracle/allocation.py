@@ -92,6 +92,7 @@ def advantages(rewards, group_off, eps=1e-6):
     """A_i = (r_i - mu) / (sigma + eps) per group, sigma the population
     standard deviation (Eq. 3).  With sigma = 0 every r_i - mu is 0 and the
     advantage is defined as exactly 0 (also when eps = 0).
+    eps is taken at its fp32 value (the library's argument type).
     Returns (adv fp32 [N], mu fp32 [P], sigma fp32 [P]); float64 inside."""
     r = np.asarray(rewards, dtype=np.float32).astype(np.float64)
     off = np.asarray(group_off, dtype=np.int64)
@@ -115,7 +116,7 @@ def advantages(rewards, group_off, eps=1e-6):
         mu_o[p], sg_o[p] = np.float32(mu), np.float32(sigma)
         for i, x in enumerate(g):
             d = x - mu
-            adv[off[p] + i] = np.float32(0.0 if d == 0.0 else d / (sigma + float(eps)))
+            adv[off[p] + i] = np.float32(0.0 if d == 0.0 else d / (sigma + float(np.float32(eps))))
     return adv, mu_o, sg_o
 
 

@@ -1,0 +1,724 @@
+// Context, paged KV bookkeeping and the C ABI entry points (include/pc.h).
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "pc_internal.h"
+
+namespace pc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+struct Slot {
+    bool used = false;
+    bool is_prompt = false;
+    int len = 0;          // tokens whose K/V are in the cache
+    int capacity = 0;     // tokens the slot's blocks can hold
+    std::vector<int32_t> blocks;
+};
+
+}  // namespace pc
+
+using namespace pc;
+
+struct pc_ctx {
+    pc_model_config m;
+    pc_cache_config c;
+    int device = 0;
+    size_t esz = 2;
+    // weights (library-owned fused copies, except embed / lm_head / final_norm)
+    const void *tok_embed = nullptr, *lm_head = nullptr;
+    const float *final_norm = nullptr;
+    std::vector<void *> wqkv, wo, wgu, wdown;
+    std::vector<float *> attn_norm, ffn_norm;
+    // KV cache
+    void *pool = nullptr;
+    int64_t n_blocks = 0;
+    int max_blocks_per_slot = 0;
+    int32_t *d_block_table = nullptr, *d_slot_len = nullptr;
+    std::vector<int32_t> h_table, h_len;
+    std::vector<int32_t> refcnt, free_blocks, free_slots;
+    std::vector<Slot> slots;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+    // activations
+    float *h = nullptr, *qkv = nullptr, *attn_scratch = nullptr;
+    void *a = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+    int32_t *d_meta = nullptr;   // row_slot | row_pos | cu_rows | prompt_slot | last_rows | copy pairs
+    int32_t *d_dec_slot = nullptr;
+    std::vector<int32_t> dec_seq;     // sequence list currently resident in d_dec_slot
+    std::vector<int32_t> stamp;
+    int32_t stamp_gen = 0;
+    // options
+    int use_graph = 1, force_simt = 0;
+    // captured decode step
+    hipGraphExec_t exec = nullptr;
+    struct {
+        const void *tokens = nullptr, *logits = nullptr;
+        hipStream_t stream = nullptr;
+        int n = -1, splits = -1;
+        uint64_t list_version = 0;
+    } gkey;
+    uint64_t list_version = 1;
+    // event timing of one kernel class on selected eager steps
+    int time_class = -1;
+    std::vector<hipEvent_t> ev_pool;
+    size_t ev_used = 0;
+
+    KvGeom geom() const {
+        KvGeom g;
+        g.pool = pool;
+        g.layer_stride = n_blocks * (int64_t)m.n_kv_heads * 2 * c.block_size * m.head_dim;
+        g.block_size = c.block_size;
+        g.n_kv_heads = m.n_kv_heads;
+        g.head_dim = m.head_dim;
+        g.max_blocks_per_slot = max_blocks_per_slot;
+        g.block_table = d_block_table;
+        return g;
+    }
+    int impl() const { return (m.dtype == PC_DTYPE_BF16 && !force_simt) ? 1 : 0; }
+    bool mfma_attention() const { return impl() == 1 && m.head_dim == 128 && (m.n_q_heads / m.n_kv_heads) <= 16; }
+};
+
+namespace {
+
+template <typename T> pc_status dev_alloc(T **p, size_t n_elems) {
+    *p = nullptr;
+    if (n_elems == 0) n_elems = 1;
+    PC_HIP(hipMalloc((void **)p, n_elems * sizeof(T)));
+    return PC_OK;
+}
+
+void free_all(pc_ctx *ctx) {
+    if (ctx->exec) (void)hipGraphExecDestroy(ctx->exec);
+    for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+    auto fr = [](const void *p) { if (p) (void)hipFree(const_cast<void *>(p)); };
+    for (auto p : ctx->wqkv) fr(p);
+    for (auto p : ctx->wo) fr(p);
+    for (auto p : ctx->wgu) fr(p);
+    for (auto p : ctx->wdown) fr(p);
+    for (auto p : ctx->attn_norm) fr(p);
+    for (auto p : ctx->ffn_norm) fr(p);
+    fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
+    fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
+    fr(ctx->d_meta); fr(ctx->d_dec_slot);
+}
+
+// uploads rows [s0, s1] of the host block table and slot lengths
+pc_status upload_slots(pc_ctx *ctx, int s0, int s1, hipStream_t st) {
+    if (s1 < s0) return PC_OK;
+    const size_t w = ctx->max_blocks_per_slot;
+    PC_HIP(hipMemcpyAsync(ctx->d_block_table + (size_t)s0 * w, ctx->h_table.data() + (size_t)s0 * w,
+                          (size_t)(s1 - s0 + 1) * w * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    PC_HIP(hipMemcpyAsync(ctx->d_slot_len + s0, ctx->h_len.data() + s0, (size_t)(s1 - s0 + 1) * sizeof(int32_t),
+                          hipMemcpyHostToDevice, st));
+    return PC_OK;
+}
+
+void write_table_row(pc_ctx *ctx, int slot) {
+    const Slot &s = ctx->slots[slot];
+    int32_t *row = ctx->h_table.data() + (size_t)slot * ctx->max_blocks_per_slot;
+    for (size_t i = 0; i < s.blocks.size(); ++i) row[i] = s.blocks[i];
+    ctx->h_len[slot] = s.len;
+}
+
+void release_slot(pc_ctx *ctx, int slot) {
+    Slot &s = ctx->slots[slot];
+    for (int32_t b : s.blocks)
+        if (--ctx->refcnt[b] == 0) ctx->free_blocks.push_back(b);
+    s = Slot();
+    ctx->free_slots.push_back(slot);
+}
+
+// Brackets a launch with an event pair when its class is being timed.
+struct Timed {
+    pc_ctx *ctx;
+    hipStream_t st;
+    bool on;
+    Timed(pc_ctx *c, int cls, hipStream_t s) : ctx(c), st(s), on(c->time_class == cls) {
+        if (on) record();
+    }
+    ~Timed() {
+        if (on) record();
+    }
+    void record() {
+        if (ctx->ev_used == ctx->ev_pool.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) {
+                on = false;
+                return;
+            }
+            ctx->ev_pool.push_back(e);
+        }
+        (void)hipEventRecord(ctx->ev_pool[ctx->ev_used++], st);
+    }
+};
+
+// One transformer layer stack over `rows` rows already embedded in ctx->h.
+// prefill: cu_rows/prompt_slot describe the prompts (matrix-core attention); row_pos given.
+// decode:  row_pos == nullptr, positions come from the device slot lengths.
+void enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t *row_pos, const int32_t *cu_rows,
+                    const int32_t *prompt_slot, int n_prompts, int max_len, int max_ctx_now, hipStream_t st) {
+    const pc_model_config &m = ctx->m;
+    const int dt = m.dtype, impl = ctx->impl();
+    const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
+    const KvGeom kv = ctx->geom();
+    for (int l = 0; l < m.n_layers; ++l) {
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, st);
+        {
+            Timed t(ctx, PC_KERNEL_GEMM_QKV, st);
+            launch_gemm(dt, impl, ctx->a, ctx->wqkv[l], ctx->qkv, rows, qd + 2 * kvd, m.d_model, EPI_STORE_F32, st);
+        }
+        launch_rope_append(dt, ctx->qkv, row_slot, row_pos, ctx->d_slot_len, ctx->rope_cos, ctx->rope_sin, rows,
+                           m.n_q_heads, kv, l, ctx->q, st);
+        if (ctx->mfma_attention()) {
+            if (row_pos)
+                launch_attention_prefill_mfma(ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
+                                              ctx->attn, st);
+            else {
+                {
+                    Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
+                    launch_attention_decode_mfma(ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l,
+                                                 max_ctx_now, ctx->attn_scratch, st);
+                }
+                launch_attention_decode_merge(row_slot, ctx->d_slot_len, rows, m.n_q_heads, max_ctx_now,
+                                              ctx->attn_scratch, ctx->attn, st);
+            }
+        } else {
+            launch_attention_simt(dt, ctx->q, row_slot, row_pos, ctx->d_slot_len, rows, m.n_q_heads, kv, l, ctx->attn,
+                                  st);
+        }
+        {
+            Timed t(ctx, PC_KERNEL_GEMM_WO, st);
+            launch_gemm(dt, impl, ctx->attn, ctx->wo[l], ctx->h, rows, m.d_model, qd, EPI_RESID_F32, st);
+        }
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->ffn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, st);
+        {
+            Timed t(ctx, PC_KERNEL_GEMM_GATE_UP, st);
+            launch_gemm(dt, impl, ctx->a, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU, st);
+        }
+        {
+            Timed t(ctx, PC_KERNEL_GEMM_DOWN, st);
+            launch_gemm(dt, impl, ctx->act, ctx->wdown[l], ctx->h, rows, m.d_model, m.d_ff, EPI_RESID_F32, st);
+        }
+    }
+}
+
+void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits, int max_ctx_now, hipStream_t st) {
+    const pc_model_config &m = ctx->m;
+    launch_embed(m.dtype, ctx->tok_embed, tokens_in, n, m.d_model, m.vocab, ctx->h, st);
+    enqueue_layers(ctx, n, ctx->d_dec_slot, nullptr, nullptr, nullptr, 0, 0, max_ctx_now, st);
+    launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, st);
+    {
+        Timed t(ctx, PC_KERNEL_GEMM_LM_HEAD, st);
+        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, st);
+    }
+    launch_advance_len(ctx->d_slot_len, ctx->d_dec_slot, n, st);
+}
+
+pc_status check_launch() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
+    return PC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *pc_last_error(void) { return g_err; }
+
+pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_cache_config *cache, pc_ctx **out) {
+    if (!model || !w || !cache || !out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: null argument");
+    *out = nullptr;
+    const pc_model_config &m = *model;
+    if (m.n_layers <= 0 || m.d_model <= 0 || m.n_q_heads <= 0 || m.n_kv_heads <= 0 || m.head_dim <= 0 || m.d_ff <= 0 ||
+        m.vocab <= 0 || !(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f))
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: non-positive model dimension");
+    if (m.dtype != PC_DTYPE_F32 && m.dtype != PC_DTYPE_BF16) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: unknown dtype");
+    if (m.n_q_heads % m.n_kv_heads) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: n_q_heads not a multiple of n_kv_heads");
+    if (m.head_dim % 2 || m.head_dim > 256) PC_FAIL(PC_ERR_UNSUPPORTED, "pc_create: head_dim must be even and <= 256");
+    if (m.d_ff % 32) PC_FAIL(PC_ERR_UNSUPPORTED, "pc_create: d_ff must be a multiple of 32");
+    if (cache->block_size <= 0 || cache->block_size % 32 || cache->block_size > 256)
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: block_size must be a multiple of 32, at most 256");
+    if (cache->max_slots <= 0 || cache->max_ctx <= 0 || cache->max_batch_rows <= 0 || cache->kv_pool_bytes <= 0)
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: non-positive cache dimension");
+    if (!w->tok_embed || !w->lm_head || !w->final_norm || !w->attn_norm || !w->wq || !w->wk || !w->wv || !w->wo ||
+        !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: null weight pointer");
+    for (int l = 0; l < m.n_layers; ++l)
+        if (!w->attn_norm[l] || !w->wq[l] || !w->wk[l] || !w->wv[l] || !w->wo[l] || !w->ffn_norm[l] || !w->w_gate[l] ||
+            !w->w_up[l] || !w->w_down[l])
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: null weight pointer in layer %d", l);
+
+    pc_ctx *ctx = new (std::nothrow) pc_ctx();
+    if (!ctx) PC_FAIL(PC_ERR_OOM, "pc_create: host allocation failed");
+    ctx->m = m;
+    ctx->c = *cache;
+    ctx->esz = (m.dtype == PC_DTYPE_F32) ? 4 : 2;
+    pc_status rc = PC_OK;
+#define TRY(expr)                 \
+    do {                          \
+        rc = (expr);              \
+        if (rc != PC_OK) {        \
+            free_all(ctx);        \
+            delete ctx;           \
+            return rc;            \
+        }                         \
+    } while (0)
+#define TRY_HIP(expr)                                                                        \
+    do {                                                                                     \
+        hipError_t e_ = (expr);                                                              \
+        if (e_ != hipSuccess) {                                                              \
+            set_error("%s failed: %s", #expr, hipGetErrorString(e_));                        \
+            free_all(ctx);                                                                   \
+            delete ctx;                                                                      \
+            return PC_ERR_HIP;                                                               \
+        }                                                                                    \
+    } while (0)
+    TRY_HIP(hipGetDevice(&ctx->device));
+    gemm_init();
+    const size_t esz = ctx->esz;
+    const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
+    hipStream_t st = nullptr;
+
+    // ---- fused weight copies
+    ctx->tok_embed = w->tok_embed;
+    ctx->lm_head = w->lm_head;
+    ctx->final_norm = (const float *)w->final_norm;
+    for (int l = 0; l < m.n_layers; ++l) {
+        void *p;
+        float *g;
+        TRY(dev_alloc((char **)&p, (size_t)(qd + 2 * kvd) * m.d_model * esz));
+        ctx->wqkv.push_back(p);
+        launch_pack_rows(m.dtype, w->wq[l], p, qd, m.d_model, 0, st);
+        launch_pack_rows(m.dtype, w->wk[l], p, kvd, m.d_model, qd, st);
+        launch_pack_rows(m.dtype, w->wv[l], p, kvd, m.d_model, qd + kvd, st);
+        TRY(dev_alloc((char **)&p, (size_t)m.d_model * qd * esz));
+        ctx->wo.push_back(p);
+        TRY_HIP(hipMemcpyAsync(p, w->wo[l], (size_t)m.d_model * qd * esz, hipMemcpyDeviceToDevice, st));
+        TRY(dev_alloc((char **)&p, (size_t)2 * m.d_ff * m.d_model * esz));
+        ctx->wgu.push_back(p);
+        launch_pack_gate_up(m.dtype, w->w_gate[l], w->w_up[l], p, m.d_ff, m.d_model, st);
+        TRY(dev_alloc((char **)&p, (size_t)m.d_model * m.d_ff * esz));
+        ctx->wdown.push_back(p);
+        TRY_HIP(hipMemcpyAsync(p, w->w_down[l], (size_t)m.d_model * m.d_ff * esz, hipMemcpyDeviceToDevice, st));
+        TRY(dev_alloc(&g, (size_t)m.d_model));
+        ctx->attn_norm.push_back(g);
+        TRY_HIP(hipMemcpyAsync(g, w->attn_norm[l], (size_t)m.d_model * 4, hipMemcpyDeviceToDevice, st));
+        TRY(dev_alloc(&g, (size_t)m.d_model));
+        ctx->ffn_norm.push_back(g);
+        TRY_HIP(hipMemcpyAsync(g, w->ffn_norm[l], (size_t)m.d_model * 4, hipMemcpyDeviceToDevice, st));
+    }
+
+    // ---- KV pool
+    const int bs = cache->block_size;
+    const int64_t block_bytes_all_layers = (int64_t)m.n_layers * m.n_kv_heads * 2 * bs * m.head_dim * (int64_t)esz;
+    ctx->n_blocks = cache->kv_pool_bytes / block_bytes_all_layers;
+    if (ctx->n_blocks <= 0 || ctx->n_blocks > 0x7fffffff) {
+        set_error("pc_create: kv_pool_bytes holds %lld blocks of %lld bytes", (long long)ctx->n_blocks,
+                  (long long)block_bytes_all_layers);
+        free_all(ctx);
+        delete ctx;
+        return PC_ERR_INVALID_ARG;
+    }
+    TRY_HIP(hipMalloc(&ctx->pool, (size_t)(ctx->n_blocks * block_bytes_all_layers)));
+    // stale cache entries are multiplied by zero probabilities: they must be finite
+    TRY_HIP(hipMemsetAsync(ctx->pool, 0, (size_t)(ctx->n_blocks * block_bytes_all_layers), st));
+    ctx->max_blocks_per_slot = (cache->max_ctx + bs - 1) / bs;
+    TRY(dev_alloc(&ctx->d_block_table, (size_t)cache->max_slots * ctx->max_blocks_per_slot));
+    TRY(dev_alloc(&ctx->d_slot_len, (size_t)cache->max_slots));
+    TRY_HIP(hipMemsetAsync(ctx->d_block_table, 0, (size_t)cache->max_slots * ctx->max_blocks_per_slot * 4, st));
+    TRY_HIP(hipMemsetAsync(ctx->d_slot_len, 0, (size_t)cache->max_slots * 4, st));
+    ctx->h_table.assign((size_t)cache->max_slots * ctx->max_blocks_per_slot, 0);
+    ctx->h_len.assign(cache->max_slots, 0);
+    ctx->refcnt.assign((size_t)ctx->n_blocks, 0);
+    ctx->free_blocks.reserve((size_t)ctx->n_blocks);
+    for (int64_t b = ctx->n_blocks - 1; b >= 0; --b) ctx->free_blocks.push_back((int32_t)b);
+    ctx->slots.resize(cache->max_slots);
+    for (int s = cache->max_slots - 1; s >= 0; --s) ctx->free_slots.push_back(s);
+    ctx->stamp.assign(cache->max_slots, 0);
+
+    // ---- rotary tables, angles in double
+    {
+        const int half = m.head_dim / 2;
+        std::vector<float> cs((size_t)cache->max_ctx * half), sn((size_t)cache->max_ctx * half);
+        for (int i = 0; i < half; ++i) {
+            const double inv = pow((double)m.rope_theta, -2.0 * i / (double)m.head_dim);
+            for (int p = 0; p < cache->max_ctx; ++p) {
+                const double ang = (double)p * inv;
+                cs[(size_t)p * half + i] = (float)cos(ang);
+                sn[(size_t)p * half + i] = (float)sin(ang);
+            }
+        }
+        TRY(dev_alloc(&ctx->rope_cos, cs.size()));
+        TRY(dev_alloc(&ctx->rope_sin, sn.size()));
+        TRY_HIP(hipMemcpy(ctx->rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice));
+        TRY_HIP(hipMemcpy(ctx->rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice));
+    }
+
+    // ---- activations
+    const size_t R = (size_t)cache->max_batch_rows;
+    TRY(dev_alloc(&ctx->h, R * m.d_model));
+    TRY(dev_alloc(&ctx->qkv, R * (qd + 2 * kvd)));
+    TRY(dev_alloc((char **)&ctx->a, R * std::max(m.d_model, qd) * esz));
+    TRY(dev_alloc((char **)&ctx->q, R * qd * esz));
+    TRY(dev_alloc((char **)&ctx->attn, R * qd * esz));
+    TRY(dev_alloc((char **)&ctx->act, R * m.d_ff * esz));
+    TRY(dev_alloc(&ctx->attn_scratch,
+                  attention_decode_scratch_floats(std::min<int>((int)R, cache->max_slots), m.n_q_heads, m.head_dim,
+                                                  cache->max_ctx)));
+    TRY(dev_alloc(&ctx->d_meta, 2 * R + 3 * (size_t)cache->max_slots + 2 * (size_t)cache->max_slots + 16));
+    TRY(dev_alloc(&ctx->d_dec_slot, (size_t)cache->max_slots));
+    TRY_HIP(hipDeviceSynchronize());
+    TRY(check_launch());
+#undef TRY
+#undef TRY_HIP
+    *out = ctx;
+    return PC_OK;
+}
+
+pc_status pc_destroy(pc_ctx *ctx) {
+    if (!ctx) return PC_OK;
+    (void)hipDeviceSynchronize();
+    free_all(ctx);
+    delete ctx;
+    return PC_OK;
+}
+
+pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_set_option: null context");
+    switch (option) {
+        case PC_OPT_USE_GRAPH: ctx->use_graph = value ? 1 : 0; break;
+        case PC_OPT_FORCE_SIMT: ctx->force_simt = value ? 1 : 0; break;
+        case PC_OPT_TIME_NEXT_STEP:
+            if (value < -1 || value > PC_KERNEL_GEMM_LM_HEAD) PC_FAIL(PC_ERR_INVALID_ARG, "pc_set_option: unknown kernel class");
+            ctx->time_class = value;
+            return PC_OK;   // a captured step stays valid
+        default: PC_FAIL(PC_ERR_INVALID_ARG, "pc_set_option: unknown option %d", option);
+    }
+    ctx->gkey.n = -1;   // any captured step is stale
+    return PC_OK;
+}
+
+pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, int32_t reset) {
+    if (!ctx || !total_ms || !launches) PC_FAIL(PC_ERR_INVALID_ARG, "pc_timing_read: null argument");
+    double tot = 0.0;
+    int64_t cnt = 0;
+    for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
+        PC_HIP(hipEventSynchronize(ctx->ev_pool[i + 1]));
+        float ms = 0.f;
+        PC_HIP(hipEventElapsedTime(&ms, ctx->ev_pool[i], ctx->ev_pool[i + 1]));
+        tot += (double)ms;
+        ++cnt;
+    }
+    *total_ms = tot;
+    *launches = cnt;
+    if (reset) ctx->ev_used = 0;
+    return PC_OK;
+}
+
+pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_kv_blocks: null context");
+    if (free_blocks) *free_blocks = (int64_t)ctx->free_blocks.size();
+    if (total_blocks) *total_blocks = ctx->n_blocks;
+    return PC_OK;
+}
+
+pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
+                            int32_t *handle_out, float *last_logits, void *stream) {
+    if (!ctx || !cu_lens || !handle_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: negative prompt count");
+    if (P == 0) return PC_OK;
+    if (!prompt_tokens || !last_logits) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
+    hipStream_t st = (hipStream_t)stream;
+    const pc_model_config &m = ctx->m;
+    const int bs = ctx->c.block_size;
+    if (cu_lens[0] != 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: cu_lens[0] must be 0");
+    int64_t need_blocks = 0;
+    for (int p = 0; p < P; ++p) {
+        const int len = cu_lens[p + 1] - cu_lens[p];
+        if (len <= 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d is empty", p);
+        if (len > ctx->c.max_ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d longer than max_ctx", p);
+        if (len > ctx->c.max_batch_rows)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d longer than max_batch_rows", p);
+        need_blocks += (len + bs - 1) / bs;
+    }
+    if ((size_t)P > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "pc_prefill_shared: out of slots");
+    if ((size_t)need_blocks > ctx->free_blocks.size())
+        PC_FAIL(PC_ERR_OOM, "pc_prefill_shared: needs %lld KV blocks, %zu free", (long long)need_blocks,
+                ctx->free_blocks.size());
+    // ---- allocate
+    int smin = ctx->c.max_slots, smax = -1;
+    for (int p = 0; p < P; ++p) {
+        const int len = cu_lens[p + 1] - cu_lens[p];
+        const int slot = ctx->free_slots.back();
+        ctx->free_slots.pop_back();
+        Slot &s = ctx->slots[slot];
+        s.used = true;
+        s.is_prompt = true;
+        s.len = len;
+        const int nb = (len + bs - 1) / bs;
+        s.capacity = nb * bs;
+        for (int i = 0; i < nb; ++i) {
+            const int32_t b = ctx->free_blocks.back();
+            ctx->free_blocks.pop_back();
+            ctx->refcnt[b] = 1;
+            s.blocks.push_back(b);
+        }
+        write_table_row(ctx, slot);
+        handle_out[p] = slot;
+        smin = std::min(smin, slot);
+        smax = std::max(smax, slot);
+    }
+    pc_status rc = upload_slots(ctx, smin, smax, st);
+    if (rc != PC_OK) return rc;
+    // ---- chunks of whole prompts, at most max_batch_rows rows each
+    const size_t R = (size_t)ctx->c.max_batch_rows, S = (size_t)ctx->c.max_slots;
+    int32_t *d_row_slot = ctx->d_meta, *d_row_pos = ctx->d_meta + R, *d_cu = ctx->d_meta + 2 * R,
+            *d_pslot = d_cu + S + 1, *d_last = d_pslot + S;
+    std::vector<int32_t> row_slot, row_pos, cu, pslot, last;
+    int p0 = 0;
+    while (p0 < P) {
+        int p1 = p0, rows = 0, max_len = 0;
+        while (p1 < P && rows + (cu_lens[p1 + 1] - cu_lens[p1]) <= (int)R) {
+            rows += cu_lens[p1 + 1] - cu_lens[p1];
+            ++p1;
+        }
+        row_slot.clear(); row_pos.clear(); cu.clear(); pslot.clear(); last.clear();
+        cu.push_back(0);
+        for (int p = p0; p < p1; ++p) {
+            const int len = cu_lens[p + 1] - cu_lens[p];
+            max_len = std::max(max_len, len);
+            for (int i = 0; i < len; ++i) {
+                row_slot.push_back(handle_out[p]);
+                row_pos.push_back(i);
+            }
+            cu.push_back(cu.back() + len);
+            pslot.push_back(handle_out[p]);
+            last.push_back(cu.back() - 1);
+        }
+        const int np = p1 - p0;
+        PC_HIP(hipMemcpyAsync(d_row_slot, row_slot.data(), (size_t)rows * 4, hipMemcpyHostToDevice, st));
+        PC_HIP(hipMemcpyAsync(d_row_pos, row_pos.data(), (size_t)rows * 4, hipMemcpyHostToDevice, st));
+        PC_HIP(hipMemcpyAsync(d_cu, cu.data(), (size_t)(np + 1) * 4, hipMemcpyHostToDevice, st));
+        PC_HIP(hipMemcpyAsync(d_pslot, pslot.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
+        PC_HIP(hipMemcpyAsync(d_last, last.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
+        launch_embed(m.dtype, ctx->tok_embed, prompt_tokens + cu_lens[p0], rows, m.d_model, m.vocab, ctx->h, st);
+        enqueue_layers(ctx, rows, d_row_slot, d_row_pos, d_cu, d_pslot, np, max_len, 0, st);
+        launch_rmsnorm(m.dtype, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, st);
+        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
+                    m.d_model, EPI_STORE_F32, st);
+        rc = check_launch();
+        if (rc != PC_OK) return rc;
+        // the metadata buffers are reused by the next chunk: pageable copies above were staged at call time
+        p0 = p1;
+    }
+    return PC_OK;
+}
+
+pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens, int32_t *seq_out,
+                  void *stream) {
+    if (!ctx || (n > 0 && (!prompt_handle || !seq_out))) PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: null argument");
+    if (n < 0 || max_new_tokens < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: negative count");
+    if (n == 0) return PC_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const int bs = ctx->c.block_size;
+    int64_t need_blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        const int h = prompt_handle[i];
+        if (h < 0 || h >= ctx->c.max_slots || !ctx->slots[h].used || !ctx->slots[h].is_prompt)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: entry %d is not a live prompt handle", i);
+        const int len = ctx->slots[h].len;
+        if (len + max_new_tokens > ctx->c.max_ctx)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: prompt length %d + %d new tokens exceeds max_ctx %d", len,
+                    max_new_tokens, ctx->c.max_ctx);
+        need_blocks += (len + max_new_tokens + bs - 1) / bs - len / bs;
+    }
+    if ((size_t)n > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "pc_fork: out of slots");
+    if ((size_t)need_blocks > ctx->free_blocks.size())
+        PC_FAIL(PC_ERR_OOM, "pc_fork: needs %lld KV blocks, %zu free", (long long)need_blocks, ctx->free_blocks.size());
+    if ((size_t)n > (size_t)ctx->c.max_slots) PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: too many sequences");
+    std::vector<int32_t> pairs;
+    int smin = ctx->c.max_slots, smax = -1;
+    for (int i = 0; i < n; ++i) {
+        const Slot &ps = ctx->slots[prompt_handle[i]];
+        const int slot = ctx->free_slots.back();
+        ctx->free_slots.pop_back();
+        Slot &s = ctx->slots[slot];
+        s.used = true;
+        s.is_prompt = false;
+        s.len = ps.len;
+        const int n_full = ps.len / bs, total = (ps.len + max_new_tokens + bs - 1) / bs;
+        for (int b = 0; b < n_full; ++b) {
+            s.blocks.push_back(ps.blocks[b]);
+            ctx->refcnt[ps.blocks[b]]++;
+        }
+        for (int b = n_full; b < total; ++b) {
+            const int32_t nb = ctx->free_blocks.back();
+            ctx->free_blocks.pop_back();
+            ctx->refcnt[nb] = 1;
+            s.blocks.push_back(nb);
+            if (b == n_full && ps.len % bs) {   // partially filled prompt block: private copy
+                pairs.push_back(ps.blocks[b]);
+                pairs.push_back(nb);
+            }
+        }
+        s.capacity = total * bs;
+        write_table_row(ctx, slot);
+        seq_out[i] = slot;
+        smin = std::min(smin, slot);
+        smax = std::max(smax, slot);
+    }
+    pc_status rc = upload_slots(ctx, smin, smax, st);
+    if (rc != PC_OK) return rc;
+    if (!pairs.empty()) {
+        int32_t *d_pairs = ctx->d_meta + 2 * (size_t)ctx->c.max_batch_rows + 3 * (size_t)ctx->c.max_slots + 8;
+        PC_HIP(hipMemcpyAsync(d_pairs, pairs.data(), pairs.size() * 4, hipMemcpyHostToDevice, st));
+        launch_copy_block(ctx->m.dtype, ctx->geom(), ctx->m.n_layers, d_pairs, (int)pairs.size() / 2, st);
+        rc = check_launch();
+    }
+    return rc;
+}
+
+pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind) {
+    if (!ctx || (n > 0 && !ids)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: null argument");
+    if (kind != 0 && kind != 1) PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: kind must be 0 (sequence) or 1 (prompt)");
+    for (int i = 0; i < n; ++i) {
+        const int s = ids[i];
+        if (s < 0 || s >= ctx->c.max_slots || !ctx->slots[s].used || ctx->slots[s].is_prompt != (kind == 1))
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: entry %d is not a live %s", i, kind ? "prompt" : "sequence");
+        for (int j = 0; j < i; ++j)
+            if (ids[j] == s) PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: entry %d repeats", i);
+    }
+    for (int i = 0; i < n; ++i) release_slot(ctx, ids[i]);
+    ctx->dec_seq.clear();
+    ctx->list_version++;
+    return PC_OK;
+}
+
+pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
+                         void *stream) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: null context");
+    if (n < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: negative count");
+    if (n == 0) return PC_OK;
+    if (!seq || !tokens_in || !logits) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: null argument");
+    if (n > ctx->c.max_batch_rows) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: n exceeds max_batch_rows");
+    hipStream_t st = (hipStream_t)stream;
+    const int32_t gen = ++ctx->stamp_gen;
+    int max_len = 0;
+    for (int i = 0; i < n; ++i) {
+        const int s = seq[i];
+        if (s < 0 || s >= ctx->c.max_slots || !ctx->slots[s].used || ctx->slots[s].is_prompt)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: entry %d is not a live sequence", i);
+        if (ctx->stamp[s] == gen) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d repeats", s);
+        ctx->stamp[s] = gen;
+        if (ctx->slots[s].len >= ctx->slots[s].capacity)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d has used its reserved tokens", s);
+        max_len = std::max(max_len, ctx->slots[s].len);
+    }
+    if ((int)ctx->dec_seq.size() != n || memcmp(ctx->dec_seq.data(), seq, (size_t)n * 4) != 0) {
+        ctx->dec_seq.assign(seq, seq + n);
+        ctx->list_version++;
+        PC_HIP(hipMemcpyAsync(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
+    }
+    const int max_ctx_now = max_len + 1;
+    const int splits = (max_ctx_now + 511) / 512;
+    if (ctx->use_graph && st != nullptr && ctx->time_class < 0) {   // the default stream cannot be captured
+        const bool hit = ctx->exec && ctx->gkey.n == n && ctx->gkey.tokens == tokens_in && ctx->gkey.logits == logits &&
+                         ctx->gkey.stream == st && ctx->gkey.splits == splits &&
+                         ctx->gkey.list_version == ctx->list_version;
+        if (!hit) {
+            if (ctx->exec) {
+                (void)hipGraphExecDestroy(ctx->exec);
+                ctx->exec = nullptr;
+            }
+            hipGraph_t graph = nullptr;
+            PC_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
+            enqueue_decode(ctx, tokens_in, n, logits, splits * 512, st);
+            hipError_t e = hipStreamEndCapture(st, &graph);
+            if (e != hipSuccess || !graph) PC_FAIL(PC_ERR_HIP, "pc_decode_step: stream capture failed: %s", hipGetErrorString(e));
+            e = hipGraphInstantiate(&ctx->exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) {
+                ctx->exec = nullptr;
+                PC_FAIL(PC_ERR_HIP, "pc_decode_step: graph instantiate failed: %s", hipGetErrorString(e));
+            }
+            ctx->gkey.n = n;
+            ctx->gkey.tokens = tokens_in;
+            ctx->gkey.logits = logits;
+            ctx->gkey.stream = st;
+            ctx->gkey.splits = splits;
+            ctx->gkey.list_version = ctx->list_version;
+        }
+        PC_HIP(hipGraphLaunch(ctx->exec, st));
+    } else {
+        enqueue_decode(ctx, tokens_in, n, logits, max_ctx_now, st);
+        ctx->time_class = -1;   // timing covers one step
+        pc_status rc = check_launch();
+        if (rc != PC_OK) return rc;
+    }
+    for (int i = 0; i < n; ++i) {
+        ctx->slots[seq[i]].len++;
+        ctx->h_len[seq[i]]++;
+    }
+    return PC_OK;
+}
+
+pc_status pc_sample(const float *logits, const int32_t *logit_row, int32_t n, int32_t vocab, float temperature,
+                    uint64_t seed, const uint64_t *seq_uid, const int32_t *step, int32_t step_base, int32_t eos_id,
+                    float eos_logit_bias, int32_t *tokens_out, float *logprob_out, uint8_t *finished, void *stream) {
+    if (n < 0 || vocab <= 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: bad count");
+    if (n == 0) return PC_OK;
+    if (!logits || !seq_uid || !tokens_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: null argument");
+    if (!(temperature > 0.f)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: temperature must be positive");
+    if (eos_id >= vocab) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: eos_id outside the vocabulary");
+    if (finished && eos_id < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: finished flags need an eos_id");
+    launch_sample(logits, logit_row, n, vocab, temperature, seed, seq_uid, step, step_base, eos_id, eos_logit_bias,
+                  tokens_out, logprob_out, finished, (hipStream_t)stream);
+    return check_launch();
+}
+
+pc_status pc_group_stats(const float *rewards, const int32_t *group_off, int32_t P, int32_t *n_pos, int32_t *n_tot,
+                         float *mean, float *var, void *stream) {
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_group_stats: negative group count");
+    if (P == 0) return PC_OK;
+    if (!rewards || !group_off) PC_FAIL(PC_ERR_INVALID_ARG, "pc_group_stats: null argument");
+    launch_group_stats(rewards, group_off, P, n_pos, n_tot, mean, var, (hipStream_t)stream);
+    return check_launch();
+}
+
+pc_status pc_select_commit(const float *p_hat, int32_t P, float p_lower, float p_upper, float p_solve, int32_t b_t,
+                           uint8_t *cls, uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts,
+                           void *stream) {
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit: negative prompt count");
+    if (!counts || (P > 0 && (!p_hat || !commit_idx))) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit: null argument");
+    if (!(p_lower <= p_upper)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit: p_lower > p_upper");
+    if (b_t > 0 && !surplus_idx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit: a cap needs surplus_idx");
+    launch_select_commit(p_hat, P, p_lower, p_upper, p_solve, b_t, cls, evict, commit_idx, surplus_idx, counts,
+                         (hipStream_t)stream);
+    return check_launch();
+}
+
+pc_status pc_advantages(const float *rewards, const int32_t *group_off, int32_t P, float eps, float *adv, float *mu,
+                        float *sigma, void *stream) {
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_advantages: negative group count");
+    if (P == 0) return PC_OK;
+    if (!rewards || !group_off || !adv) PC_FAIL(PC_ERR_INVALID_ARG, "pc_advantages: null argument");
+    if (!(eps >= 0.f)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_advantages: negative eps");
+    launch_advantages(rewards, group_off, P, eps, adv, mu, sigma, (hipStream_t)stream);
+    return check_launch();
+}
+
+}  // extern "C"

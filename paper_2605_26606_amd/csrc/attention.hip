@@ -1,0 +1,396 @@
+// Grouped-query causal attention over the paged KV cache (the attention of the
+// policy pi_theta(o_t | q, o_<t), Section 3.1).
+//
+//   attention_simt_kernel      plain ALU, any dtype / head_dim <= 256: the fp32 model path
+//   attention_prefill_mfma     bf16, head_dim 128: 16 query positions of one head per wave
+//   attention_decode_mfma      bf16, head_dim 128: the query heads that share a kv head (<= 16)
+//                              of one sequence per block, split over the context, + merge pass
+//
+// The matrix-core kernels share one inner loop.  Per 32-token tile it forms
+//   S^T[token][column] = K[token][:] . Q[column][:]      (two 16x16x32 products per 32 of head_dim)
+//   O[column][:]      += P[column][token] V[token][:]    (eight 16x16x32 products)
+// where a "column" is a query row: a head (decode) or a position (prefill).
+// K is stored [token][head_dim] and V transposed [head_dim][token] inside each
+// block, so both products read 16 contiguous bytes per lane straight from
+// global memory; no LDS staging is needed because every K/V byte is used by
+// exactly one wave.
+#include "pc_internal.h"
+
+namespace pc {
+
+static constexpr int WAVE = 64;
+
+__device__ inline float wave_max_f(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+__device__ inline float wave_sum_f(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+
+// =====================================================================================
+// plain-ALU attention: one wave per (row, query head)
+// =====================================================================================
+template <typename T>
+__global__ __launch_bounds__(64) void attention_simt_kernel(const T *__restrict__ q,
+                                                            const int32_t *__restrict__ row_slot,
+                                                            const int32_t *__restrict__ row_pos,
+                                                            const int32_t *__restrict__ slot_len, int hq, KvGeom kv,
+                                                            int layer, T *__restrict__ out) {
+    __shared__ float qs[256];
+    __shared__ float ps[WAVE];
+    const int head = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
+    const int hd = kv.head_dim, bs = kv.block_size;
+    const int slot = row_slot[r];
+    const int pos = row_pos ? row_pos[r] : slot_len[slot];
+    const int ctx = pos + 1;
+    const int g = head / (hq / kv.n_kv_heads);
+    const float scale = 1.0f / sqrtf((float)hd);
+    for (int i = lane; i < hd; i += WAVE) qs[i] = to_f32(q[((int64_t)r * hq + head) * hd + i]) * scale;
+    __syncthreads();
+    const T *base = (const T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)g * kv.head_elems();
+    const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
+    float m = -INFINITY, l = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = 0; c0 < ctx; c0 += WAVE) {
+        const int key = c0 + lane;
+        float s = -INFINITY;
+        if (key < ctx) {
+            const T *kp = base + (int64_t)table[key / bs] * kv.block_elems() + (int64_t)(key % bs) * hd;
+            float d = 0.f;
+            for (int i = 0; i < hd; ++i) d = fmaf(qs[i], to_f32(kp[i]), d);
+            s = d;
+        }
+        const float m_new = fmaxf(m, wave_max_f(s));
+        const float p = (key < ctx) ? expf(s - m_new) : 0.f;
+        const float corr = expf(m - m_new);
+        l = l * corr + wave_sum_f(p);
+        m = m_new;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[i] *= corr;
+        ps[lane] = p;
+        __syncthreads();
+        const int nk = min(WAVE, ctx - c0);
+        for (int j = 0; j < nk; ++j) {
+            const int kj = c0 + j;
+            const T *vp = base + (int64_t)table[kj / bs] * kv.block_elems() + (int64_t)bs * hd + (kj % bs);
+            const float pj = ps[j];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int c = lane + WAVE * i;
+                if (c < hd) acc[i] = fmaf(pj, to_f32(vp[(int64_t)c * bs]), acc[i]);
+            }
+        }
+        __syncthreads();
+    }
+    const float inv = 1.0f / l;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int c = lane + WAVE * i;
+        if (c < hd) out[((int64_t)r * hq + head) * hd + c] = from_f32<T>(acc[i] * inv);
+    }
+}
+
+void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, const int32_t *row_pos,
+                           const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
+                           hipStream_t s) {
+    if (rows <= 0) return;
+    dim3 grid(hq, rows);
+    if (dtype == PC_DTYPE_F32)
+        attention_simt_kernel<float><<<grid, 64, 0, s>>>((const float *)q, row_slot, row_pos, slot_len, hq, kv, layer,
+                                                         (float *)out);
+    else
+        attention_simt_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, row_slot, row_pos, slot_len, hq, kv,
+                                                          layer, (bf16_t *)out);
+}
+
+// =====================================================================================
+// matrix-core attention, head_dim = 128
+// =====================================================================================
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+static constexpr int HD = 128;
+static constexpr float LOG2E = 1.4426950408889634f;
+
+// 16x16x32 operand layout (wave of 64 lanes, i = lane%16, g = lane/16):
+//   a: A[row i][k = 8g .. 8g+7]     b: B[k = 8g .. 8g+7][col i]     d[v]: D[row 4g+v][col i]
+struct AttnState {
+    float m;        // running max of column lane%16 (same on the 4 lanes of a column)
+    float l;        // this lane's share of the running sum of column lane%16
+    f32x4 o[8];     // O[column 4g+v][16*nn + i]
+};
+
+__device__ inline bf16x8 ld_frag(const bf16_t *p) {
+    u32x4 t = *(const u32x4 *)p;
+    return __builtin_bit_cast(bf16x8, t);
+}
+
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+    return (uint32_t)f32_to_bf16(a).x | ((uint32_t)f32_to_bf16(b).x << 16);
+}
+
+// Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end.
+// Tokens > col_limit (this lane's column) or >= tok_end are masked.
+__device__ inline void attend_tiles(const bf16_t *__restrict__ head_base, int64_t block_elems,
+                                    const int32_t *__restrict__ table, int bs, const bf16x8 (&qf)[4], int tile_begin,
+                                    int tile_step, int tok_end, int col_limit, float scale_log2, AttnState &st) {
+    const int lane = threadIdx.x % WAVE, i = lane % 16, g = lane / 16;
+    const int krow = 8 * (i / 4) + (i % 4);   // tile u reads token krow + 4u: lane (column, g) then owns tokens 8g..8g+7
+    for (int t0 = tile_begin; t0 < tok_end; t0 += tile_step) {
+        const int tin = t0 % bs;
+        const bf16_t *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
+        const bf16_t *vb = kb + (int64_t)bs * HD;
+        bf16x8 ka[2][4], vf[8];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld_frag(kb + (int64_t)(tin + krow + 4 * u) * HD + 32 * kk + 8 * g);
+#pragma unroll
+        for (int nn = 0; nn < 8; ++nn) vf[nn] = ld_frag(vb + (int64_t)(16 * nn + i) * bs + tin + 8 * g);
+
+        f32x4 s[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[u][kk], qf[kk], s[u], 0, 0, 0);
+        }
+        // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
+        float mx = -INFINITY;
+        bool ok[2][4];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int tok = t0 + 8 * g + 4 * u + v;
+                ok[u][v] = (tok <= col_limit) && (tok < tok_end);
+                if (ok[u][v]) mx = fmaxf(mx, s[u][v]);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+        const float m_new = fmaxf(st.m, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = exp2f((st.m - m_use) * scale_log2);   // st.m = -inf -> 0
+        float p[2][4], psum = 0.f;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                p[u][v] = ok[u][v] ? exp2f((s[u][v] - m_use) * scale_log2) : 0.f;
+                psum += p[u][v];
+            }
+        st.l = st.l * corr + psum;
+        st.m = m_new;
+        float c4[4];
+#pragma unroll
+        for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
+        u32x4 pw = {pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]), pack_bf16x2(p[1][0], p[1][1]),
+                    pack_bf16x2(p[1][2], p[1][3])};
+        const bf16x8 pa = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+        for (int nn = 0; nn < 8; ++nn) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) st.o[nn][v] *= c4[v];
+            st.o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vf[nn], st.o[nn], 0, 0, 0);
+        }
+    }
+}
+
+__device__ inline void state_init(AttnState &st) {
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int nn = 0; nn < 8; ++nn) st.o[nn] = (f32x4){0.f, 0.f, 0.f, 0.f};
+}
+
+// ---------------------------------------------------------------- prefill
+// grid (query tiles of 16, q heads, prompts), one wave per block
+__global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const bf16_t *__restrict__ q,
+                                                                    const int32_t *__restrict__ cu_rows,
+                                                                    const int32_t *__restrict__ prompt_slot, int hq,
+                                                                    KvGeom kv, int layer, bf16_t *__restrict__ out) {
+    const int p = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 16;
+    const int row0 = cu_rows[p], len = cu_rows[p + 1] - row0;
+    if (q0 >= len) return;
+    const int lane = threadIdx.x, i = lane % 16, g = lane / 16;
+    const int slot = prompt_slot[p];
+    const int kvh = head / (hq / kv.n_kv_heads);
+    const bf16_t *head_base = (const bf16_t *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
+    const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
+    const bool col_ok = (q0 + i) < len;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        if (col_ok)
+            qf[kk] = ld_frag(q + ((int64_t)(row0 + q0 + i) * hq + head) * HD + 32 * kk + 8 * g);
+        else
+            qf[kk] = __builtin_bit_cast(bf16x8, (u32x4){0, 0, 0, 0});
+    }
+    AttnState st;
+    state_init(st);
+    const int tok_end = min(q0 + 16, len);
+    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, 0, 32, tok_end, col_ok ? q0 + i : -1,
+                 LOG2E / sqrtf((float)HD), st);
+    float l = st.l;
+    l += __shfl_xor(l, 16, WAVE);
+    l += __shfl_xor(l, 32, WAVE);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int col = 4 * g + v;
+        const float lc = __shfl(l, col, WAVE);
+        if (q0 + col < len) {
+            const float inv = 1.0f / lc;
+            bf16_t *o = out + ((int64_t)(row0 + q0 + col) * hq + head) * HD;
+#pragma unroll
+            for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = f32_to_bf16(st.o[nn][v] * inv);
+        }
+    }
+}
+
+void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
+                                   int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+    if (n_prompts <= 0 || max_len <= 0) return;
+    dim3 grid((max_len + 15) / 16, hq, n_prompts);
+    attention_prefill_mfma_kernel<<<grid, 64, 0, s>>>((const bf16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
+                                                      (bf16_t *)out);
+}
+
+// ---------------------------------------------------------------- decode
+static constexpr int SPLIT = 512;      // tokens per block
+static constexpr int DEC_WAVES = 4;
+
+// scratch layout per (row, q head, split): ml[2] = (max, sum), o[HD] (unnormalised)
+size_t attention_decode_scratch_floats(int rows, int hq, int hd, int max_ctx) {
+    size_t splits = (size_t)(max_ctx + SPLIT - 1) / SPLIT;
+    return (size_t)rows * hq * splits * (hd + 2);
+}
+
+// grid (splits, kv heads, rows), 4 waves per block; wave w takes the tiles w, w+4, ... of the split
+__global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t *__restrict__ q,
+                                                                    const int32_t *__restrict__ row_slot,
+                                                                    const int32_t *__restrict__ slot_len, int hq,
+                                                                    KvGeom kv, int layer, int max_splits,
+                                                                    float *__restrict__ part_ml,
+                                                                    float *__restrict__ part_o) {
+    __shared__ float sm[DEC_WAVES][16], sl[DEC_WAVES][16];
+    __shared__ float so[DEC_WAVES][16][HD];
+    const int sp = blockIdx.x, kvh = blockIdx.y, r = blockIdx.z;
+    const int slot = row_slot[r];
+    const int ctx = slot_len[slot] + 1;
+    const int beg = sp * SPLIT;
+    if (beg >= ctx) return;
+    const int end = min(ctx, beg + SPLIT);
+    const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE, i = lane % 16, g = lane / 16;
+    const int rep = hq / kv.n_kv_heads;
+    const bf16_t *head_base = (const bf16_t *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
+    const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
+    bf16x8 qf[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+        if (i < rep)
+            qf[kk] = ld_frag(q + ((int64_t)r * hq + kvh * rep + i) * HD + 32 * kk + 8 * g);
+        else
+            qf[kk] = __builtin_bit_cast(bf16x8, (u32x4){0, 0, 0, 0});
+    }
+    AttnState st;
+    state_init(st);
+    const float scale_log2 = LOG2E / sqrtf((float)HD);
+    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, 32 * DEC_WAVES, end, ctx - 1,
+                 scale_log2, st);
+    // ---- combine the four waves
+    float l = st.l;
+    l += __shfl_xor(l, 16, WAVE);
+    l += __shfl_xor(l, 32, WAVE);
+    if (g == 0) {
+        sm[wave][i] = st.m;
+        sl[wave][i] = l;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        const int col = 4 * g + v;
+        float M = sm[0][col];
+#pragma unroll
+        for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+        const float mw = sm[wave][col];
+        const float fw = (mw == -INFINITY) ? 0.f : exp2f((mw - M) * scale_log2);
+#pragma unroll
+        for (int nn = 0; nn < 8; ++nn) so[wave][col][16 * nn + i] = st.o[nn][v] * fw;
+    }
+    __syncthreads();
+    // thread t sums column t/16.. : 16 columns x 128 values = 2048 values over 256 threads
+    for (int e = tid; e < rep * HD; e += 256) {
+        const int col = e / HD, c = e % HD;
+        float v = 0.f;
+#pragma unroll
+        for (int w = 0; w < DEC_WAVES; ++w) v += so[w][col][c];
+        const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * max_splits + sp;
+        part_o[idx * HD + c] = v;
+    }
+    if (tid < rep) {
+        const int col = tid;
+        float M = sm[0][col];
+#pragma unroll
+        for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+        float L = 0.f;
+#pragma unroll
+        for (int w = 0; w < DEC_WAVES; ++w) {
+            const float mw = sm[w][col];
+            L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
+        }
+        const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * max_splits + sp;
+        part_ml[2 * idx] = M;
+        part_ml[2 * idx + 1] = L;
+    }
+}
+
+// grid (q heads, rows), 128 threads: one per head_dim column
+__global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32_t *__restrict__ row_slot,
+                                                                     const int32_t *__restrict__ slot_len, int hq,
+                                                                     int max_splits, const float *__restrict__ part_ml,
+                                                                     const float *__restrict__ part_o,
+                                                                     bf16_t *__restrict__ out) {
+    const int head = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
+    const int ctx = slot_len[row_slot[r]] + 1;
+    const int ns = (ctx + SPLIT - 1) / SPLIT;
+    const int64_t base = ((int64_t)r * hq + head) * max_splits;
+    const float scale_log2 = LOG2E / sqrtf((float)HD);
+    float M = -INFINITY;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[2 * (base + s)]);
+    float L = 0.f, acc = 0.f;
+    for (int s = 0; s < ns; ++s) {
+        const float f = exp2f((part_ml[2 * (base + s)] - M) * scale_log2);
+        L += f * part_ml[2 * (base + s) + 1];
+        acc += f * part_o[(base + s) * HD + c];
+    }
+    out[((int64_t)r * hq + head) * HD + c] = f32_to_bf16(acc / L);
+}
+
+void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
+                                  KvGeom kv, int layer, int max_ctx_now, float *scratch, hipStream_t s) {
+    if (rows <= 0) return;
+    const int max_splits = (max_ctx_now + SPLIT - 1) / SPLIT;
+    float *part_ml = scratch;
+    float *part_o = scratch + (size_t)rows * hq * max_splits * 2;
+    dim3 grid(max_splits, kv.n_kv_heads, rows);
+    attention_decode_mfma_kernel<<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer, max_splits,
+                                                      part_ml, part_o);
+}
+
+void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int max_ctx_now,
+                                   float *scratch, void *out, hipStream_t s) {
+    if (rows <= 0) return;
+    const int max_splits = (max_ctx_now + SPLIT - 1) / SPLIT;
+    const float *part_ml = scratch;
+    const float *part_o = scratch + (size_t)rows * hq * max_splits * 2;
+    dim3 mgrid(hq, rows);
+    attention_decode_merge_kernel<<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, max_splits, part_ml, part_o,
+                                                        (bf16_t *)out);
+}
+
+}  // namespace pc

@@ -1,0 +1,130 @@
+// Internal declarations shared by the library's translation units.
+// Not part of the C ABI (see include/pc.h for that).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/pc.h"
+
+namespace pc {
+
+// ---------------------------------------------------------------- bf16
+struct bf16_t {
+    uint16_t x;
+};
+
+__host__ __device__ inline float bf16_to_f32(bf16_t v) {
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v.x << 16;
+    return c.f;
+}
+// round to nearest even (inputs are finite here)
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    uint32_t u = c.u + 0x7FFFu + ((c.u >> 16) & 1u);
+    bf16_t r;
+    r.x = (uint16_t)(u >> 16);
+    return r;
+}
+
+__device__ inline float to_f32(float v) { return v; }
+__device__ inline float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ inline T from_f32(float f);
+template <> __device__ inline float from_f32<float>(float f) { return f; }
+template <> __device__ inline bf16_t from_f32<bf16_t>(float f) { return f32_to_bf16(f); }
+
+// ---------------------------------------------------------------- errors
+void set_error(const char *fmt, ...);
+#define PC_FAIL(code, ...)          \
+    do {                            \
+        ::pc::set_error(__VA_ARGS__); \
+        return (code);              \
+    } while (0)
+#define PC_HIP(expr)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess) {                                                             \
+            ::pc::set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(e_), __FILE__, __LINE__); \
+            return PC_ERR_HIP;                                                              \
+        }                                                                                   \
+    } while (0)
+
+// ---------------------------------------------------------------- KV cache geometry
+// Pool layout: [layer][block][kv_head][K | V^T] with
+//   K    [block_size][head_dim]   (a token's key is contiguous)
+//   V^T  [head_dim][block_size]   (a head-dim row's values over the block's
+//                                  tokens are contiguous: the layout the
+//                                  P.V matrix-core product consumes)
+struct KvGeom {
+    void *pool;
+    int64_t layer_stride;   // elements between layers
+    int32_t block_size;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    int32_t max_blocks_per_slot;
+    const int32_t *block_table;   // device [max_slots][max_blocks_per_slot]
+    __host__ __device__ int64_t block_elems() const { return (int64_t)n_kv_heads * 2 * block_size * head_dim; }
+    __host__ __device__ int64_t head_elems() const { return (int64_t)2 * block_size * head_dim; }
+};
+
+// Epilogues of the projection GEMMs
+enum Epilogue {
+    EPI_STORE_F32 = 0,   // C fp32 [M,N]
+    EPI_RESID_F32 = 1,   // C fp32 [M,N] += product (residual stream update)
+    EPI_SWIGLU = 2,      // rows of W come in chunks of 64: 32 gate rows then the 32 matching up rows;
+                         // C (model dtype) [M, N/2] = silu(gate) * up
+    EPI_STORE_T = 3,     // C model dtype [M,N]
+};
+
+// ---------------------------------------------------------------- kernel launchers
+// (each validates nothing: callers pass shapes that the context has checked)
+void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows, int d, int vocab, float *h,
+                  hipStream_t s);
+// out[r] = norm(h[src_row ? src_row[r] : r]) * gain, in the model dtype
+void launch_rmsnorm(int dtype, const float *h, const int32_t *src_row, const float *gain, int rows, int d,
+                    float eps, void *out, hipStream_t s);
+// C = A[M,K] * W[N,K]^T with the given epilogue.  impl 0: plain ALU, 1: matrix cores (bf16 only)
+void gemm_init();   // once per process: raises the dynamic-LDS limit of the matrix-core kernels
+void launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
+                 hipStream_t s);
+// Rotates q and k at each row's position, writes q (model dtype) and appends k, v to the cache.
+//   qkv fp32 [rows, (hq+2hkv)*hd]; row_slot [rows]; row_pos [rows] or NULL (then pos = slot_len[slot])
+void launch_rope_append(int dtype, const float *qkv, const int32_t *row_slot, const int32_t *row_pos,
+                        const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
+                        KvGeom kv, int layer, void *q_out, hipStream_t s);
+// Attention of each row's query heads over its slot's cache, positions 0..pos (plain ALU).
+void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, const int32_t *row_pos,
+                           const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
+                           hipStream_t s);
+// Matrix-core attention (bf16).  Prefill: rows of each prompt are contiguous and start at position 0.
+void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
+                                   int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s);
+// Decode: one query row per sequence; split-KV with a merge pass.  scratch: fp32 workspace.
+void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
+                                  KvGeom kv, int layer, int max_ctx_now, float *scratch, hipStream_t s);
+void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int max_ctx_now,
+                                   float *scratch, void *out, hipStream_t s);
+size_t attention_decode_scratch_floats(int rows, int hq, int hd, int max_ctx);
+
+void launch_advance_len(int32_t *slot_len, const int32_t *row_slot, int rows, hipStream_t s);
+void launch_copy_block(int dtype, KvGeom kv, int n_layers, const int32_t *src_dst_pairs, int n_pairs, hipStream_t s);
+void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t s);
+
+void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, uint64_t seed,
+                   const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
+                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, hipStream_t s);
+void launch_group_stats(const float *rewards, const int32_t *off, int P, int32_t *n_pos, int32_t *n_tot, float *mean,
+                        float *var, hipStream_t s);
+void launch_select_commit(const float *p_hat, int P, float lo, float hi, float solve, int b_t, uint8_t *cls,
+                          uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts, hipStream_t s);
+void launch_advantages(const float *rewards, const int32_t *off, int P, float eps, float *adv, float *mu, float *sigma,
+                       hipStream_t s);
+
+// weight repacking at context creation
+void launch_pack_rows(int dtype, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
+                      hipStream_t s);   // dst[dst_row0 + r] = src[r]
+void launch_pack_gate_up(int dtype, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s);
+
+}  // namespace pc

@@ -1,0 +1,274 @@
+// Token sampling o_t ~ softmax(logits / T) (Section 3.1; Section 4.2: T = 1.0,
+// top_p = 1.0) by inverse CDF with a Philox4x32-10 uniform.
+//
+// One block of 16 waves per row.  The row is read from HBM once: every wave
+// keeps an online (max, sum) of a contiguous segment, the block locates the
+// segment whose cumulative weight crosses u*Z, then narrows it twice more
+// (16 sub-segments, then an in-order wavefront scan), re-reading only that
+// segment.  Sums are accumulated in double so that the selected token agrees
+// with an in-order double-precision CDF except within rounding of a boundary.
+#include "pc_internal.h"
+
+namespace pc {
+
+static constexpr int WAVE = 64;
+static constexpr int SAMPLE_WAVES = 16;
+
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies
+__device__ inline void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0, uint32_t k1,
+                                     uint32_t out[4]) {
+    const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        const uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += W0; k1 += W1;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ inline double wave_sum_d(double v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, WAVE);
+    return v;
+}
+__device__ inline float wave_max_f32(float v) {
+#pragma unroll
+    for (int o = WAVE / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, WAVE));
+    return v;
+}
+
+template <int VEC>
+__device__ inline void load_scaled(const float *__restrict__ x, int idx, int end, float inv_t, int eos_id,
+                                   float eos_bias, float (&v)[VEC], bool (&ok)[VEC]) {
+    if (VEC == 4 && idx + 3 < end) {
+        const float4 t = *(const float4 *)(x + idx);
+        v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) ok[c] = true;
+    } else {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            ok[c] = (idx + c) < end;
+            v[c] = ok[c] ? x[idx + c] : 0.f;
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        v[c] = v[c] * inv_t;
+        if (idx + c == eos_id) v[c] += eos_bias;
+    }
+}
+
+__device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+template <int VEC>
+__global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
+    const float *__restrict__ logits, const int32_t *__restrict__ logit_row, int vocab, float inv_t, uint64_t seed,
+    const uint64_t *__restrict__ seq_uid, const int32_t *__restrict__ step, int step_base, int eos_id, float eos_bias,
+    int32_t *__restrict__ tokens_out, float *__restrict__ logprob_out, uint8_t *__restrict__ finished) {
+    __shared__ float s_wm[SAMPLE_WAVES];
+    __shared__ double s_ws[SAMPLE_WAVES];
+    __shared__ double s_sub[SAMPLE_WAVES];
+    __shared__ float s_u;
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
+    if (finished && finished[row]) {   // block-uniform
+        if (tid == 0) {
+            tokens_out[row] = eos_id;
+            if (logprob_out) logprob_out[row] = 0.f;
+        }
+        return;
+    }
+    const float *x = logits + (int64_t)(logit_row ? logit_row[row] : row) * vocab;
+    if (tid == 0) {
+        const uint64_t uid = seq_uid[row];
+        const uint32_t st = (uint32_t)(step_base + (step ? step[row] : 0));
+        uint32_t r[4];
+        philox4x32_10(st, (uint32_t)uid, (uint32_t)(uid >> 32), 0u, (uint32_t)seed, (uint32_t)(seed >> 32), r);
+        s_u = ((float)(r[0] >> 9) + 0.5f) * (1.0f / 8388608.0f);   // exact in fp32, inside (0,1)
+    }
+    constexpr int STRIDE = WAVE * VEC;
+    // ---- level 1: online (max, sum) per contiguous wave segment
+    const int seg = round_up((vocab + SAMPLE_WAVES - 1) / SAMPLE_WAVES, STRIDE);
+    {
+        const int b = min(vocab, wave * seg), e = min(vocab, b + seg);
+        float m = -INFINITY;
+        double s = 0.0;
+        for (int base = b; base < e; base += STRIDE) {
+            float v[VEC];
+            bool ok[VEC];
+            load_scaled<VEC>(x, base + lane * VEC, e, inv_t, eos_id, eos_bias, v, ok);
+            float lm = -INFINITY;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c)
+                if (ok[c]) lm = fmaxf(lm, v[c]);
+            if (lm > m) {
+                s *= (double)expf(m - lm);   // m = -inf -> 0
+                m = lm;
+            }
+#pragma unroll
+            for (int c = 0; c < VEC; ++c)
+                if (ok[c]) s += (double)expf(v[c] - m);
+        }
+        const float wm = wave_max_f32(m);
+        const double ws = wave_sum_d(m == -INFINITY ? 0.0 : s * (double)expf(m - wm));
+        if (lane == 0) {
+            s_wm[wave] = wm;
+            s_ws[wave] = ws;
+        }
+    }
+    __syncthreads();
+    float M = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < SAMPLE_WAVES; ++w) M = fmaxf(M, s_wm[w]);
+    double Z = 0.0, segw[SAMPLE_WAVES];
+#pragma unroll
+    for (int w = 0; w < SAMPLE_WAVES; ++w) {
+        segw[w] = (s_wm[w] == -INFINITY) ? 0.0 : s_ws[w] * (double)expf(s_wm[w] - M);
+        Z += segw[w];
+    }
+    const double target = (double)s_u * Z;
+    int k = -1;
+    double before = 0.0, run = 0.0;
+#pragma unroll
+    for (int w = 0; w < SAMPLE_WAVES; ++w) {
+        if (k < 0 && run + segw[w] > target) {
+            k = w;
+            before = run;
+        }
+        run += segw[w];
+    }
+    if (k < 0) {   // rounding left no crossing: the last segment with weight
+        run = 0.0;
+#pragma unroll
+        for (int w = 0; w < SAMPLE_WAVES; ++w) {
+            if (segw[w] > 0.0) {
+                k = w;
+                before = run;
+            }
+            run += segw[w];
+        }
+    }
+    double rem = target - before;
+    const int kb = min(vocab, k * seg), ke = min(vocab, kb + seg);
+    // ---- level 2: 16 sub-segments of segment k
+    const int sub = round_up((seg + SAMPLE_WAVES - 1) / SAMPLE_WAVES, STRIDE);
+    {
+        const int b = min(ke, kb + wave * sub), e = min(ke, b + sub);
+        double s = 0.0;
+        for (int base = b; base < e; base += STRIDE) {
+            float v[VEC];
+            bool ok[VEC];
+            load_scaled<VEC>(x, base + lane * VEC, e, inv_t, eos_id, eos_bias, v, ok);
+#pragma unroll
+            for (int c = 0; c < VEC; ++c)
+                if (ok[c]) s += (double)expf(v[c] - M);
+        }
+        s = wave_sum_d(s);
+        if (lane == 0) s_sub[wave] = s;
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    int j = -1;
+    before = 0.0;
+    run = 0.0;
+#pragma unroll
+    for (int w = 0; w < SAMPLE_WAVES; ++w) {
+        const double sw = s_sub[w];
+        if (j < 0 && run + sw > rem) {
+            j = w;
+            before = run;
+        }
+        run += sw;
+    }
+    if (j < 0) {
+        run = 0.0;
+#pragma unroll
+        for (int w = 0; w < SAMPLE_WAVES; ++w) {
+            if (s_sub[w] > 0.0) {
+                j = w;
+                before = run;
+            }
+            run += s_sub[w];
+        }
+        if (j < 0) j = 0;
+    }
+    rem -= before;
+    // ---- level 3: wave 0 scans sub-segment j in index order
+    const int jb = min(ke, kb + j * sub), je = min(ke, jb + sub);
+    double running = 0.0;
+    int token = -1, last_pos = -1;
+    float tok_x = 0.f;
+    for (int base = jb; base < je && token < 0; base += STRIDE) {
+        float v[VEC];
+        bool ok[VEC];
+        const int idx = base + lane * VEC;
+        load_scaled<VEC>(x, idx, je, inv_t, eos_id, eos_bias, v, ok);
+        double pre[VEC], lsum = 0.0;
+        int my_last = -1;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const double w = ok[c] ? (double)expf(v[c] - M) : 0.0;
+            lsum += w;
+            pre[c] = lsum;
+            if (w > 0.0) my_last = idx + c;
+        }
+        double incl = lsum;
+#pragma unroll
+        for (int o = 1; o < WAVE; o <<= 1) {
+            const double t = __shfl_up(incl, o, WAVE);
+            if (lane >= o) incl += t;
+        }
+        const double excl = running + (incl - lsum);
+        int cross = -1;
+#pragma unroll
+        for (int c = VEC - 1; c >= 0; --c)
+            if (ok[c] && excl + pre[c] > rem) cross = c;
+        const unsigned long long bal = __ballot(cross >= 0);
+        if (bal) {
+            const int src = __ffsll((long long)bal) - 1;
+            const int t = __shfl(idx + (cross < 0 ? 0 : cross), src, WAVE);
+            float xv = 0.f;
+#pragma unroll
+            for (int c = 0; c < VEC; ++c)
+                if (c == cross) xv = v[c];
+            tok_x = __shfl(xv, src, WAVE);
+            token = t;
+        }
+        running += __shfl(incl, WAVE - 1, WAVE);
+        // remember the last index that carried weight, for the no-crossing case
+        int ml = my_last;
+#pragma unroll
+        for (int o = WAVE / 2; o > 0; o >>= 1) ml = max(ml, __shfl_xor(ml, o, WAVE));
+        last_pos = max(last_pos, ml);
+    }
+    if (token < 0) {
+        token = last_pos >= 0 ? last_pos : max(0, je - 1);
+        tok_x = x[token] * inv_t + (token == eos_id ? eos_bias : 0.f);
+    }
+    if (lane == 0) {
+        tokens_out[row] = token;
+        if (logprob_out) logprob_out[row] = (float)((double)tok_x - (double)M - log(Z));
+        if (finished && token == eos_id) finished[row] = 1;
+    }
+}
+
+void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, uint64_t seed,
+                   const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
+                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, hipStream_t s) {
+    if (n <= 0) return;
+    const float inv_t = 1.0f / temperature;
+    const bool vec = (vocab % 4 == 0) && (((uintptr_t)logits) % 16 == 0);
+    if (vec)
+        sample_kernel<4><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
+                                                           step_base, eos_id, eos_bias, tokens_out, logprob_out,
+                                                           finished);
+    else
+        sample_kernel<1><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
+                                                           step_base, eos_id, eos_bias, tokens_out, logprob_out,
+                                                           finished);
+}
+
+}  // namespace pc

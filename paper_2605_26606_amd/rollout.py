@@ -1,0 +1,198 @@
+"""Host driver of one Pilot-Commit sampling step (Algorithm 1 without the
+replay buffer): shared-prefix prefill, pilot rollouts, per-prompt statistics,
+filter / commit set, commit rollouts on the kept prompts only, advantages over
+pilot U commit.  Every step of the path runs in the library's kernels; this
+file only sequences pc_* calls and holds device buffers.  The synthetic reward
+rules (the stand-in for the paper's verifier, Section 3.3 R(q,o)) are applied
+here with elementwise tensor ops, as a caller would apply its own verifier.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def _seq_uids(prompt_uids: np.ndarray, rollout_indices) -> np.ndarray:
+    """uid = prompt uid * 2^16 + rollout index, prompt-major."""
+    r = np.asarray(list(rollout_indices), dtype=np.int64)
+    return (np.asarray(prompt_uids, dtype=np.int64)[:, None] * 65536 + r[None, :]).reshape(-1)
+
+
+def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_logits: torch.Tensor,
+             seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
+             eos_logit_bias: float = 0.0, stream=None, keep_logits_rows: Optional[np.ndarray] = None,
+             poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None):
+    """Samples one completion per entry of `handles` (prompt handles, one per
+    sequence).  Token 0 comes from the prompt's prefill logits
+    (first_logits[logit_rows[i]]); tokens 1.. from decode steps.
+
+    Returns dict(tokens [n, T] int32 device (eos_id-padded after the end when
+    EOS is on), lengths [n] int32 device, steps_run, logits (optional: list per
+    step of the requested rows, for parity tests))."""
+    dev = first_logits.device
+    n = len(handles)
+    V = ctx.vocab
+    T = int(new_tokens)
+    hist = torch.zeros((T, max(n, 1)), dtype=torch.int32, device=dev)
+    out = dict(tokens=hist[:, :n].t().contiguous(), lengths=torch.zeros(n, dtype=torch.int32, device=dev),
+               steps_run=0, logits=[])
+    if n == 0 or T == 0:
+        return out
+    seqs = B.pc_fork(ctx, handles, T, stream)
+    uid_d = torch.from_numpy(np.ascontiguousarray(seq_uids, dtype=np.int64)).to(dev)
+    rows_d = torch.from_numpy(np.ascontiguousarray(logit_rows, dtype=np.int32)).to(dev)
+    cur = torch.zeros(n, dtype=torch.int32, device=dev)
+    logits = torch.empty((n, V), dtype=torch.float32, device=dev)
+    finished = torch.zeros(n, dtype=torch.uint8, device=dev) if eos_id >= 0 else None
+    keep = None if keep_logits_rows is None else torch.as_tensor(keep_logits_rows, dtype=torch.long, device=dev)
+    B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, None,
+                finished, stream)
+    hist[0, :n].copy_(cur)
+    if keep is not None:
+        out["logits"].append(first_logits[rows_d.long()[keep]].clone())
+    steps = 1
+    for t in range(1, T):
+        if finished is not None and t % poll_every == 0 and bool(finished.all().item()):
+            hist[t:, :n] = eos_id
+            break
+        if time_every > 0 and t % time_every == time_every // 2:
+            # this step runs eagerly with HIP events around every launch of one kernel class
+            B.pc_set_option(ctx, B.PC_OPT_TIME_NEXT_STEP, time_class)
+            if timed_steps is not None:
+                timed_steps.append((t, n))
+        B.pc_decode_step(ctx, seqs, cur, logits, stream)
+        if keep is not None:
+            out["logits"].append(logits[keep].clone())
+        B.pc_sample(logits, None, n, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, None,
+                    finished, stream)
+        hist[t, :n].copy_(cur)
+        steps += 1
+    B.pc_release(ctx, seqs, 0)
+    toks = hist[:, :n].t().contiguous()
+    if eos_id >= 0:
+        is_eos = (toks == eos_id)
+        first = torch.where(is_eos.any(1), is_eos.float().argmax(1).to(torch.int32) + 1,
+                            torch.full((n,), T, dtype=torch.int32, device=dev))
+        lengths = first.to(torch.int32)
+    else:
+        lengths = torch.full((n,), T, dtype=torch.int32, device=dev)
+    out.update(tokens=toks, lengths=lengths, steps_run=steps)
+    return out
+
+
+def synthetic_rewards(rule: str, tokens: torch.Tensor, lengths: torch.Tensor, prompt_uid_per_seq: torch.Tensor,
+                      p_q_per_seq: Optional[torch.Tensor] = None, reward_u: Optional[torch.Tensor] = None):
+    """Binary reward per sequence from its last generated token (the EOS
+    itself when the sequence stopped on it)."""
+    last = tokens.gather(1, (lengths.long() - 1).clamp(min=0)[:, None])[:, 0].long()
+    if rule == "last_even":
+        r = (last % 2 == 0)
+    elif rule == "last_mod7":
+        r = (last % 7 == prompt_uid_per_seq.long() % 7)
+    elif rule == "bernoulli":
+        r = reward_u < p_q_per_seq
+    else:
+        raise ValueError(rule)
+    return r.to(torch.float32)
+
+
+def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: np.ndarray, prompt_uids: np.ndarray,
+                      seed: int, eos_id: int = -1, eos_logit_bias: float = 0.0, p_q: Optional[np.ndarray] = None,
+                      reward_u: Optional[np.ndarray] = None, stream=None, eps: float = 1e-6, time_class: int = -1,
+                      time_every: int = 0, timed_steps: Optional[list] = None, timings: Optional[dict] = None):
+    """One pilot + commit step for the batch of prompts.  Returns a dict of
+    device tensors / host counts mirroring the quantities of Algorithm 1.
+    `timings` (optional dict) receives prefill_ms / pilot_ms / commit_ms from
+    events on the current stream."""
+    dev = prompt_tokens.device
+    P = len(cu_lens) - 1
+    V = ctx.vocab
+    npil, ncom, T = wl.n_pilot, wl.n_commit, wl.new_tokens
+    uids = np.asarray(prompt_uids, dtype=np.int64)
+    last_logits = torch.empty((P, V), dtype=torch.float32, device=dev)
+    marks = []
+
+    def mark():
+        if timings is not None:
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            marks.append(e)
+
+    mark()
+    handles = B.pc_prefill_shared(ctx, prompt_tokens, cu_lens, last_logits, stream)
+    mark()
+    uid_d = torch.from_numpy(uids).to(dev)
+    pq_d = None if p_q is None else torch.from_numpy(np.asarray(p_q, np.float32)).to(dev)
+    ru_d = None if reward_u is None else torch.from_numpy(np.asarray(reward_u, np.float32)).to(dev)
+
+    # ---- pilot pass: n_pilot rollouts for every prompt
+    rows = np.repeat(np.arange(P, dtype=np.int32), npil)
+    tkw = dict(time_class=time_class, time_every=time_every)
+    ts_p = [] if timed_steps is not None else None
+    ts_c = [] if timed_steps is not None else None
+    g = generate(ctx, handles[rows], rows, last_logits, _seq_uids(uids, range(npil)), T, wl.temperature, seed,
+                 eos_id, eos_logit_bias, stream, timed_steps=ts_p, **tkw)
+    mark()
+    rows_d = torch.from_numpy(rows).to(dev).long()
+    pilot_r = synthetic_rewards(wl.reward, g["tokens"], g["lengths"], uid_d[rows_d],
+                                None if pq_d is None else pq_d[rows_d],
+                                None if ru_d is None else ru_d[:, :npil].reshape(-1))
+    off = torch.arange(P + 1, dtype=torch.int32, device=dev) * npil
+    n_pos = torch.empty(P, dtype=torch.int32, device=dev)
+    n_tot = torch.empty(P, dtype=torch.int32, device=dev)
+    p_hat = torch.empty(P, dtype=torch.float32, device=dev)
+    var = torch.empty(P, dtype=torch.float32, device=dev)
+    B.pc_group_stats(pilot_r, off, n_pos, n_tot, p_hat, var, stream)
+    cls = torch.empty(P, dtype=torch.uint8, device=dev)
+    evict = torch.empty(P, dtype=torch.uint8, device=dev)
+    commit_idx = torch.empty(P, dtype=torch.int32, device=dev)
+    surplus_idx = torch.empty(P, dtype=torch.int32, device=dev)
+    counts = torch.empty(4, dtype=torch.int32, device=dev)
+    B.pc_select_commit(p_hat, P, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t, cls, evict, commit_idx, surplus_idx,
+                       counts, stream)
+    counts_h = counts.cpu().numpy()            # the one read-back the method needs: the commit pass's size
+    K = int(counts_h[0])
+    kept = commit_idx[:K].cpu().numpy()
+
+    # ---- commit pass: n_commit more rollouts for the kept prompts only; prefix KV is reused
+    mark()
+    crow = np.repeat(kept.astype(np.int32), ncom)
+    gc = generate(ctx, handles[crow], crow, last_logits, _seq_uids(uids[kept], range(npil, npil + ncom)), T,
+                  wl.temperature, seed, eos_id, eos_logit_bias, stream, timed_steps=ts_c, **tkw)
+    if timed_steps is not None:
+        # (pass, step, sequences, prompts whose prefix those sequences share)
+        timed_steps.extend(("pilot", t, n, P) for t, n in ts_p)
+        timed_steps.extend(("commit", t, n, K) for t, n in ts_c)
+    mark()
+    crow_d = torch.from_numpy(crow).to(dev).long()
+    commit_r = synthetic_rewards(wl.reward, gc["tokens"], gc["lengths"], uid_d[crow_d],
+                                 None if pq_d is None else pq_d[crow_d],
+                                 None if ru_d is None else ru_d[torch.from_numpy(kept).to(dev).long(), npil:npil + ncom]
+                                 .reshape(-1)) if K else torch.zeros(0, dtype=torch.float32, device=dev)
+    B.pc_release(ctx, handles, 1)
+
+    # ---- advantages over the union group of every kept prompt
+    kept_d = torch.from_numpy(kept).to(dev).long()
+    union_r = torch.cat([pilot_r.view(P, npil)[kept_d], commit_r.view(K, ncom)], dim=1).contiguous()
+    uoff = torch.arange(K + 1, dtype=torch.int32, device=dev) * (npil + ncom)
+    adv = torch.zeros(K * (npil + ncom), dtype=torch.float32, device=dev)
+    mu = torch.zeros(max(K, 1), dtype=torch.float32, device=dev)
+    sigma = torch.zeros(max(K, 1), dtype=torch.float32, device=dev)
+    if K:
+        B.pc_advantages(union_r.view(-1), uoff, eps, adv, mu, sigma, stream)
+    n_tok = int(g["lengths"].sum().item()) + (int(gc["lengths"].sum().item()) if K else 0)
+    if timings is not None:
+        torch.cuda.current_stream().synchronize()
+        timings.update(prefill_ms=marks[0].elapsed_time(marks[1]), pilot_ms=marks[1].elapsed_time(marks[2]),
+                       commit_ms=marks[3].elapsed_time(marks[4]))
+    return dict(pilot_tokens=g["tokens"].view(P, npil, T), pilot_lens=g["lengths"].view(P, npil),
+                pilot_rewards=pilot_r.view(P, npil), n_pos=n_pos, n_tot=n_tot, p_hat=p_hat, var=var, cls=cls,
+                evict=evict, commit_idx=kept, surplus_idx=surplus_idx[:int(counts_h[1])].cpu().numpy(),
+                counts=counts_h, commit_tokens=gc["tokens"].view(K, ncom, T), commit_lens=gc["lengths"].view(K, ncom),
+                commit_rewards=commit_r.view(K, ncom), union_rewards=union_r, advantages=adv.view(K, npil + ncom),
+                mu=mu[:K], sigma=sigma[:K], rollouts=P * npil + K * ncom, tokens_generated=n_tok,
+                decode_steps=g["steps_run"] + gc["steps_run"])

@@ -1,0 +1,260 @@
+"""GPU parity of the decoder path (pc_prefill_shared, pc_fork, pc_decode_step,
+pc_sample) against the oracle, teacher-forced: the GPU generates freely; the
+oracle is fed the GPU's own token history and recomputes the logits of every
+position from scratch (brute force).
+
+Logits: max-abs error <= 1e-4 for fp32 models, <= 2e-2 for bf16 models, both
+times max(1, max|logit|) (the bounds are stated for logits of order 1, which
+is what the workloads' N(0, 0.02) init gives; tests that inflate the weights
+to sharpen the attention scale the bound with the logit magnitude).
+
+Tokens: a sampled token is an integer decided by floating point, so the
+decision is compared in the kernel's precision: the oracle's sampler, given
+the logits the GPU sampled from and the same uniform, must pick the same
+token on >= 99.9 % of positions.  Sampling from the oracle's OWN logits is
+checked as well: >= 99.9 % for fp32 models; for bf16 models the agreement is
+bounded by the logit error itself -- a uniform lands between the two sides'
+CDF boundaries with probability ~ 0.4 sqrt(V) rms(logit error) for a
+near-uniform distribution over V tokens -- so there it must stay above
+1 - max(1 %, 1.5 sqrt(V) rms error).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import decoder, philox, sampler
+from gpu_util import make_ctx, say, side_stream
+
+pytestmark = pytest.mark.gpu
+
+C1 = workloads.WORKLOADS["C1"]
+# a small bf16 model with the head geometry of the large ones (head_dim 128, 6 query heads per kv head)
+BF = workloads.scaled(C1, dtype="bf16", d_model=256, n_q_heads=12, n_kv_heads=2, head_dim=128, d_ff=640,
+                      vocab=2048, n_layers=3, rope_theta=1.0e6).model
+BF4 = workloads.scaled(C1, dtype="bf16", d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=1024,
+                       vocab=4096, n_layers=2, rope_theta=1.0e6).model
+
+
+def _teacher_forced(model, w, prompt, gen_tokens, gpu_logits, uid, seed, temperature, eos_id=-1, bias=0.0):
+    """gpu_logits: [T, V] the logits the GPU sampled each generated token from.
+    Returns (scaled max-abs error, sum of squared errors, count, agreement of the oracle's sampler on
+    the GPU's logits, agreement of the oracle's sampler on its own logits)."""
+    T = len(gen_tokens)
+    seq = np.concatenate([prompt, gen_tokens])
+    want = decoder.forward_full(model, w, seq[:-1], rows=np.arange(len(prompt) - 1, len(seq) - 1))
+    # the error of a bf16 pipeline is relative to the logit magnitude: the bound is stated for
+    # logits of order 1 (the workloads' N(0, 0.02) init) and scales up for inflated test weights
+    diff = want - gpu_logits
+    err = float(np.abs(diff).max()) / max(1.0, float(np.abs(want).max()))
+    same = own = 0
+    for t in range(T):
+        u = philox.sampling_uniform(seed, uid, t)
+        same += int(sampler.sample_token(gpu_logits[t], temperature, u, eos_id, bias)[0] == gen_tokens[t])
+        own += int(sampler.sample_token(want[t], temperature, u, eos_id, bias)[0] == gen_tokens[t])
+    assert np.abs(want).max() > 0.05, "degenerate logits make the comparison empty"
+    return err, float((diff ** 2).sum()), diff.size, same, own
+
+
+def _run_generate(model, w_cpu, prompts_list, G, T, seed, ctx_kw, opts=(), temperature=1.0, stream=True,
+                  eos_id=-1, bias=0.0):
+    import paper_2605_26606_amd as pc
+    ctx = make_ctx(model, w_cpu, **ctx_kw)
+    for o, v in opts:
+        pc.pc_set_option(ctx, o, v)
+    lens = [len(p) for p in prompts_list]
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    toks = torch.from_numpy(np.concatenate(prompts_list).astype(np.int32)).cuda()
+    P = len(prompts_list)
+    st = side_stream() if stream else torch.cuda.current_stream()
+    with torch.cuda.stream(st):
+        last = torch.empty((P, model.vocab), dtype=torch.float32, device="cuda")
+        handles = pc.pc_prefill_shared(ctx, toks, cu, last)
+        rows = np.repeat(np.arange(P, dtype=np.int32), G)
+        uids = (rows.astype(np.int64) * 65536 + np.tile(np.arange(G), P))
+        n = P * G
+        g = pc.generate(ctx, handles[rows], rows, last, uids, T, temperature, seed, eos_id, bias,
+                        keep_logits_rows=np.arange(n))
+        pc.pc_release(ctx, handles, 1)
+    torch.cuda.synchronize()
+    free, total = pc.pc_kv_blocks(ctx)
+    assert free == total, "released everything, yet %d of %d blocks are free" % (free, total)
+    logits = torch.stack(g["logits"]).cpu().numpy()          # [steps, n, V]
+    out = dict(tokens=g["tokens"].cpu().numpy(), lengths=g["lengths"].cpu().numpy(), logits=logits,
+               last=last.cpu().numpy(), uids=uids, rows=rows)
+    ctx.close()
+    return out
+
+
+def _check(model, w, prompts_list, out, seed, tol, seqs, temperature=1.0, eos_id=-1, bias=0.0):
+    tot = same = own = cnt = 0
+    worst = sq = 0.0
+    for i in seqs:
+        L = int(out["lengths"][i])
+        gen = out["tokens"][i, :L]
+        gl = out["logits"][:L, i]
+        err, s2, c, a_same, a_own = _teacher_forced(model, w, prompts_list[out["rows"][i]], gen, gl,
+                                                    int(out["uids"][i]), seed, temperature, eos_id, bias)
+        worst = max(worst, err)
+        sq += s2
+        cnt += c
+        tot += L
+        same += a_same
+        own += a_own
+    rms = math.sqrt(sq / cnt)
+    say("max-abs logit error %.3g (rms %.3g) over %d positions; tokens: %d/%d from the GPU's logits, %d/%d from "
+        "the oracle's own" % (worst, rms, tot, same, tot, own, tot))
+    assert worst <= tol
+    assert same >= math.ceil(0.999 * tot)
+    if model.dtype == "fp32":
+        assert own >= math.ceil(0.999 * tot)
+    else:
+        assert own >= math.floor((1.0 - max(0.01, 1.5 * math.sqrt(model.vocab) * rms)) * tot)
+
+
+def test_fp32_c1_prefill_and_decode():
+    say("fp32 C1: 8 prompts x 32, G=4, 16 new tokens")
+    m = C1.model
+    w = workloads.perturb_norm_gains(workloads.make_weights(m, 1), 7)
+    prompts = list(workloads.make_prompts(8, 32, m.vocab, 2))
+    out = _run_generate(m, w, prompts, 4, 16, 3, dict(block_size=32, kv_pool_bytes=64 << 20, max_slots=256,
+                                                     max_ctx=128, max_batch_rows=512))
+    # prefill logits of every prompt
+    for q in range(8):
+        want = decoder.forward_full(m, w, prompts[q], rows=[31])[0]
+        assert np.abs(want - out["last"][q]).max() <= 1e-4
+    _check(m, w, prompts, out, 3, 1e-4, range(32))
+
+
+def test_fp32_ragged_prompts_partial_blocks_chunks_and_larger_weights():
+    # prompt lengths that leave partially filled blocks (copy-on-fork), several prefill
+    # chunks (max_batch_rows < total tokens), contexts that cross block boundaries while
+    # decoding, and weights large enough that attention is far from uniform
+    say("fp32 ragged prompts, std 0.15")
+    m = workloads.scaled(C1, n_q_heads=6, n_kv_heads=2, d_model=96, head_dim=16, d_ff=160, vocab=300).model
+    w = workloads.perturb_norm_gains(workloads.make_weights(m, 5, std=0.15), 8)
+    lens = [1, 31, 32, 33, 64, 70, 5, 97]
+    toks, cu = workloads.make_ragged_prompts(lens, m.vocab, 4)
+    prompts = [toks[cu[i]:cu[i + 1]] for i in range(len(lens))]
+    out = _run_generate(m, w, prompts, 3, 40, 11, dict(block_size=32, kv_pool_bytes=32 << 20, max_slots=64,
+                                                      max_ctx=160, max_batch_rows=128), temperature=0.8)
+    for q in range(len(lens)):
+        want = decoder.forward_full(m, w, prompts[q], rows=[lens[q] - 1])[0]
+        assert np.abs(want - out["last"][q]).max() <= 1e-4 * max(1.0, np.abs(want).max())
+    _check(m, w, prompts, out, 11, 1e-4, range(0, 24, 2), temperature=0.8)
+
+
+def test_bf16_plain_alu_path():
+    say("bf16 small model, plain-ALU kernels")
+    import paper_2605_26606_amd as pc
+    w = workloads.perturb_norm_gains(workloads.make_weights(BF, 2), 9)
+    prompts = list(workloads.make_prompts(3, 40, BF.vocab, 6))
+    out = _run_generate(BF, w, prompts, 2, 12, 5, dict(block_size=32, kv_pool_bytes=64 << 20, max_slots=32,
+                                                      max_ctx=128, max_batch_rows=256),
+                        opts=[(pc.PC_OPT_FORCE_SIMT, 1)])
+    _check(BF, w, prompts, out, 5, 2e-2, range(6))
+
+
+@pytest.mark.parametrize("model,lens,G,T,bs,std", [
+    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.02),  # the workloads' init: absolute 2e-2 bound
+    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.05),  # 6 query heads per kv head, ragged, partial blocks
+    (BF4, [600, 17, 520], 3, 40, 32, 0.05),       # contexts beyond one 512-token split, 4 heads per kv head
+])
+def test_bf16_matrix_core_path(model, lens, G, T, bs, std):
+    say("bf16 matrix-core path lens=%s G=%d T=%d std=%g" % (lens, G, T, std))
+    w = workloads.perturb_norm_gains(workloads.make_weights(model, 3, std=std), 10)
+    toks, cu = workloads.make_ragged_prompts(lens, model.vocab, 8)
+    prompts = [toks[cu[i]:cu[i + 1]] for i in range(len(lens))]
+    out = _run_generate(model, w, prompts, G, T, 21, dict(block_size=bs, kv_pool_bytes=256 << 20, max_slots=64,
+                                                         max_ctx=1024, max_batch_rows=1024))
+    for q in range(len(lens)):
+        want = decoder.forward_full(model, w, prompts[q], rows=[lens[q] - 1])[0]
+        assert np.abs(want - out["last"][q]).max() <= 2e-2 * max(1.0, np.abs(want).max())
+        if std == 0.02:
+            assert np.abs(want).max() < 2.0 and np.abs(want - out["last"][q]).max() <= 2e-2
+    _check(model, w, prompts, out, 21, 2e-2, range(0, len(lens) * G, 2))
+
+
+def test_graph_replay_equals_eager_and_is_deterministic():
+    say("graph vs eager, bf16")
+    import paper_2605_26606_amd as pc
+    w = workloads.make_weights(BF, 4, std=0.05)
+    prompts = list(workloads.make_prompts(4, 100, BF.vocab, 12))
+    kw = dict(block_size=64, kv_pool_bytes=128 << 20, max_slots=64, max_ctx=1024, max_batch_rows=512)
+    a = _run_generate(BF, w, prompts, 4, 30, 2, kw, opts=[(pc.PC_OPT_USE_GRAPH, 1)])
+    b = _run_generate(BF, w, prompts, 4, 30, 2, kw, opts=[(pc.PC_OPT_USE_GRAPH, 0)])
+    c = _run_generate(BF, w, prompts, 4, 30, 2, kw, opts=[(pc.PC_OPT_USE_GRAPH, 1)])
+    assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(a["logits"], b["logits"])
+    assert np.array_equal(a["tokens"], c["tokens"]) and np.array_equal(a["logits"], c["logits"])
+
+
+def test_eos_stops_sequences_fp32():
+    say("fp32 C1 with a biased EOS id")
+    m = C1.model
+    w = workloads.make_weights(m, 1)
+    prompts = list(workloads.make_prompts(4, 20, m.vocab, 2))
+    eos = workloads.make_eos_id(m.vocab, 4)
+    bias = math.log(m.vocab / 6.0)
+    out = _run_generate(m, w, prompts, 4, 24, 3, dict(block_size=32, kv_pool_bytes=32 << 20, max_slots=64,
+                                                     max_ctx=64, max_batch_rows=128), eos_id=eos, bias=bias)
+    lens = out["lengths"]
+    assert (lens < 24).any()
+    for i in range(16):
+        L = int(lens[i])
+        assert (out["tokens"][i, :L - 1] != eos).all()
+        if L < 24:
+            assert out["tokens"][i, L - 1] == eos and (out["tokens"][i, L:] == eos).all()
+    _check(m, w, prompts, out, 3, 1e-4, range(16), eos_id=eos, bias=bias)
+
+
+def test_error_paths_leave_state_unchanged():
+    import paper_2605_26606_amd as pc
+    m = C1.model
+    w = workloads.make_weights(m, 1)
+    ctx = make_ctx(m, w, block_size=32, kv_pool_bytes=2 * 2 * 2 * 32 * 32 * 4 * 6, max_slots=8, max_ctx=96,
+                   max_batch_rows=64)
+    free0, total = pc.pc_kv_blocks(ctx)
+    assert total == 6
+    toks = torch.zeros(200, dtype=torch.int32, device="cuda")
+    last = torch.empty((1, m.vocab), device="cuda")
+    with pytest.raises(pc.PcError) as e:          # prompt longer than max_batch_rows
+        pc.pc_prefill_shared(ctx, toks, [0, 65], last)
+    assert e.value.code == -1
+    with pytest.raises(pc.PcError) as e:          # empty prompt
+        pc.pc_prefill_shared(ctx, toks, [0, 0], last)
+    assert e.value.code == -1
+    last7 = torch.empty((7, m.vocab), device="cuda")
+    with pytest.raises(pc.PcError) as e:          # 7 prompts x 1 block > 6 blocks
+        pc.pc_prefill_shared(ctx, toks, np.arange(8) * 8, last7)
+    assert e.value.code == -2
+    assert pc.pc_kv_blocks(ctx)[0] == free0
+    h = pc.pc_prefill_shared(ctx, toks, [0, 40], last)
+    assert pc.pc_kv_blocks(ctx)[0] == free0 - 2
+    with pytest.raises(pc.PcError) as e:          # 3 forks x (1 private + ...) blocks do not fit
+        pc.pc_fork(ctx, [h[0]] * 5, 20)
+    assert e.value.code == -2
+    assert pc.pc_kv_blocks(ctx)[0] == free0 - 2
+    with pytest.raises(pc.PcError):               # beyond max_ctx
+        pc.pc_fork(ctx, [h[0]], 100)
+    with pytest.raises(pc.PcError):               # not a prompt handle
+        pc.pc_fork(ctx, [7], 4)
+    s = pc.pc_fork(ctx, [h[0], h[0]], 2)
+    cur = torch.zeros(2, dtype=torch.int32, device="cuda")
+    lg = torch.empty((2, m.vocab), device="cuda")
+    with pytest.raises(pc.PcError):               # repeated sequence
+        pc.pc_decode_step(ctx, [s[0], s[0]], cur, lg)
+    with pytest.raises(pc.PcError):               # a prompt handle is not a sequence
+        pc.pc_decode_step(ctx, [h[0]], cur, lg)
+    for _ in range(24):                           # 40 + 2 new tokens reserve up to the block end: 64 tokens
+        pc.pc_decode_step(ctx, s, cur, lg)
+    with pytest.raises(pc.PcError):               # reserved tokens used up
+        pc.pc_decode_step(ctx, s, cur, lg)
+    pc.pc_release(ctx, s, 0)
+    with pytest.raises(pc.PcError):
+        pc.pc_release(ctx, s, 0)                  # already released
+    pc.pc_release(ctx, h, 1)
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == total
+    ctx.close()

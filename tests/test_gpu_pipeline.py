@@ -1,0 +1,118 @@
+"""GPU parity of one whole Pilot-Commit step on the tiny fp32 workload:
+tokens teacher-forced against the oracle, and every allocation output
+(statistics, classes, eviction, commit set, advantages, rollout counts)
+bit-exact given the rewards."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import allocation, decoder, philox, rollout as orollout, sampler
+from gpu_util import make_ctx, say, side_stream
+
+pytestmark = pytest.mark.gpu
+
+
+def _step(wl, w, prompts, uids, seed, eos_id=-1, bias=0.0, p_q=None, reward_u=None, **ctx_kw):
+    import paper_2605_26606_amd as pc
+    ctx = make_ctx(wl.model, w, **ctx_kw)
+    P, Lp = prompts.shape
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    toks = torch.from_numpy(prompts.reshape(-1).astype(np.int32)).cuda()
+    with torch.cuda.stream(side_stream()):
+        out = pc.pilot_commit_step(ctx, wl, toks, cu, uids, seed, eos_id, bias, p_q, reward_u)
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1]
+    ctx.close()
+    return {k: (v.cpu().numpy() if isinstance(v, torch.Tensor) else v) for k, v in out.items()}
+
+
+def _check_allocation(wl, got):
+    P, npil, ncom = got["pilot_rewards"].shape[0], wl.n_pilot, wl.n_commit
+    off = (np.arange(P + 1) * npil).astype(np.int32)
+    n_pos, n_tot, p_hat, var = allocation.group_stats(got["pilot_rewards"].reshape(-1), off)
+    assert np.array_equal(got["n_pos"], n_pos) and np.array_equal(got["n_tot"], n_tot)
+    assert np.array_equal(got["p_hat"], p_hat) and np.array_equal(got["var"], var)
+    cls, evict, commit, surplus, counts = allocation.select_commit(p_hat, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t)
+    assert np.array_equal(got["cls"], cls) and np.array_equal(got["evict"], evict)
+    assert np.array_equal(got["commit_idx"], commit) and np.array_equal(got["surplus_idx"], surplus)
+    assert np.array_equal(got["counts"], counts)
+    K = len(commit)
+    assert got["commit_tokens"].shape[:2] == (K, ncom)
+    union = np.concatenate([got["pilot_rewards"][commit], got["commit_rewards"]], axis=1)
+    assert np.array_equal(got["union_rewards"], union)
+    adv, mu, sigma = allocation.advantages(union.reshape(-1), (np.arange(K + 1) * (npil + ncom)).astype(np.int32))
+    assert np.array_equal(got["advantages"].reshape(-1), adv)
+    assert np.array_equal(got["mu"], mu) and np.array_equal(got["sigma"], sigma)
+    assert got["rollouts"] == allocation.rollouts_generated(P, npil, K, ncom)
+    assert got["tokens_generated"] == int(got["pilot_lens"].sum() + got["commit_lens"].sum())
+
+
+def test_c1_whole_step_matches_oracle():
+    wl = workloads.WORKLOADS["C1"]
+    say("C1 whole step")
+    w = workloads.make_weights(wl.model, wl.seed_weights)
+    prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, wl.model.vocab, wl.seed_prompts)
+    uids = workloads.make_prompt_uids(wl.n_prompts)
+    got = _step(wl, w, prompts, uids, wl.seed_sampler, block_size=32, kv_pool_bytes=64 << 20, max_slots=256,
+                max_ctx=64, max_batch_rows=256)
+    want = orollout.pilot_commit_step(wl, w, prompts, uids, wl.seed_sampler)
+    # free-running: on this fp32 model the two sides pick the same tokens unless a uniform lands
+    # within ~1e-6 of a CDF boundary; where they do not, fall back to the teacher-forced comparison
+    same = np.array_equal(got["pilot_tokens"], want["pilot_tokens"])
+    say("free-running pilot tokens identical: %s" % same)
+    if same and np.array_equal(got["commit_idx"], want["commit_idx"]):
+        assert np.array_equal(got["commit_tokens"], want["commit_tokens"])
+        assert np.array_equal(got["pilot_rewards"], want["pilot_rewards"])
+        assert np.array_equal(got["advantages"], want["advantages"])
+        assert got["rollouts"] == want["rollouts"] and got["tokens_generated"] == want["tokens_generated"]
+    else:
+        tot = ok = 0
+        for q in range(wl.n_prompts):
+            for j in range(wl.n_pilot):
+                seq = np.concatenate([prompts[q], got["pilot_tokens"][q, j]])
+                lg = decoder.forward_full(wl.model, w, seq[:-1], rows=np.arange(wl.prompt_len - 1, len(seq) - 1))
+                for t in range(wl.new_tokens):
+                    u = philox.sampling_uniform(wl.seed_sampler, philox.seq_uid(uids[q], j), t)
+                    ok += int(sampler.sample_token(lg[t], 1.0, u)[0] == got["pilot_tokens"][q, j, t])
+                    tot += 1
+        assert ok >= math.ceil(0.999 * tot)
+    # rewards follow the workload's rule; allocation follows the rewards, bit-exactly
+    assert np.array_equal(got["pilot_rewards"], (got["pilot_tokens"][:, :, -1] % 2 == 0).astype(np.float32))
+    _check_allocation(wl, got)
+    # commit rollouts are teacher-forced too (rollout indices n_pilot..)
+    for a, q in enumerate(got["commit_idx"][:3]):
+        j = 1
+        seq = np.concatenate([prompts[q], got["commit_tokens"][a, j]])
+        lg = decoder.forward_full(wl.model, w, seq[:-1], rows=np.arange(wl.prompt_len - 1, len(seq) - 1))
+        for t in range(wl.new_tokens):
+            u = philox.sampling_uniform(wl.seed_sampler, philox.seq_uid(uids[q], wl.n_pilot + j), t)
+            assert sampler.sample_token(lg[t], 1.0, u)[0] == got["commit_tokens"][a, j, t]
+
+
+def test_bernoulli_rewards_cap_and_empty_commit():
+    # Beta-Bernoulli rewards populate all three classes; a cap b_t leaves surplus survivors
+    base = workloads.WORKLOADS["C1"]
+    wl = workloads.scaled(base, n_prompts=24, prompt_len=8, new_tokens=4, reward="bernoulli", b_t=5)
+    say("bernoulli rewards, cap 5")
+    w = workloads.make_weights(wl.model, 1)
+    prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, wl.model.vocab, 2)
+    uids = workloads.make_prompt_uids(wl.n_prompts, first=100)
+    p_q = workloads.make_success_probs(wl.n_prompts, 5)
+    ru = workloads.make_reward_uniforms(wl.n_prompts, wl.n_pilot + wl.n_commit, 5)
+    got = _step(wl, w, prompts, uids, 9, p_q=p_q, reward_u=ru, block_size=32, kv_pool_bytes=64 << 20,
+                max_slots=256, max_ctx=32, max_batch_rows=256)
+    assert np.array_equal(got["pilot_rewards"], (ru[:, :4] < p_q[:, None]).astype(np.float32))
+    assert got["counts"][0] == 5 and got["counts"][1] > 0 and got["counts"][2] > 0 and got["counts"][3] > 0
+    assert np.array_equal(got["commit_rewards"],
+                          (ru[got["commit_idx"], 4:] < p_q[got["commit_idx"], None]).astype(np.float32))
+    _check_allocation(wl, got)
+    # a batch in which every prompt is too hard: nothing is committed, nothing breaks
+    wl0 = workloads.scaled(wl, b_t=0)
+    got = _step(wl0, w, prompts, uids, 9, p_q=np.zeros(wl.n_prompts, np.float32), reward_u=ru, block_size=32,
+                kv_pool_bytes=64 << 20, max_slots=256, max_ctx=32, max_batch_rows=256)
+    assert got["counts"][0] == 0 and got["counts"][3] == wl.n_prompts and got["rollouts"] == wl.n_prompts * 4
+    assert got["advantages"].shape == (0, 8)
+    _check_allocation(wl0, got)
