@@ -57,6 +57,8 @@ struct pc_ctx {
     void *a = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
     int32_t *d_meta = nullptr;   // row_slot | row_pos | cu_rows | prompt_slot | last_rows | copy pairs
     int32_t *d_dec_slot = nullptr;
+    float *slices = nullptr;       // split-K slices of the decode projections
+    size_t slice_cap = 0;
     std::vector<int32_t> dec_seq;     // sequence list currently resident in d_dec_slot
     std::vector<int32_t> stamp;
     int32_t stamp_gen = 0;
@@ -67,7 +69,7 @@ struct pc_ctx {
     struct {
         const void *tokens = nullptr, *logits = nullptr;
         hipStream_t stream = nullptr;
-        int n = -1, splits = -1;
+        int n = -1;
         uint64_t list_version = 0;
     } gkey;
     uint64_t list_version = 1;
@@ -112,7 +114,7 @@ void free_all(pc_ctx *ctx) {
     for (auto p : ctx->ffn_norm) fr(p);
     fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
     fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
-    fr(ctx->d_meta); fr(ctx->d_dec_slot);
+    fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices);
 }
 
 // uploads rows [s0, s1] of the host block table and slot lengths
@@ -168,20 +170,27 @@ struct Timed {
 // One transformer layer stack over `rows` rows already embedded in ctx->h.
 // prefill: cu_rows/prompt_slot describe the prompts (matrix-core attention); row_pos given.
 // decode:  row_pos == nullptr, positions come from the device slot lengths.
-void enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t *row_pos, const int32_t *cu_rows,
-                    const int32_t *prompt_slot, int n_prompts, int max_len, int max_ctx_now, hipStream_t st) {
+// Returns the number of split-K slices of the last down projection still to be added to ctx->h
+// (1: none pending); the caller's next launch_rmsnorm folds them in.
+int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t *row_pos, const int32_t *cu_rows,
+                   const int32_t *prompt_slot, int n_prompts, int max_len, hipStream_t st) {
     const pc_model_config &m = ctx->m;
     const int dt = m.dtype, impl = ctx->impl();
     const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     const KvGeom kv = ctx->geom();
+    const int n_splits = attention_decode_splits(rows, m.n_kv_heads, ctx->c.max_ctx);
+    int pending = 1;
     for (int l = 0; l < m.n_layers; ++l) {
-        launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, st);
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending,
+                       st);
+        int s_qkv;
         {
             Timed t(ctx, PC_KERNEL_GEMM_QKV, st);
-            launch_gemm(dt, impl, ctx->a, ctx->wqkv[l], ctx->qkv, rows, qd + 2 * kvd, m.d_model, EPI_STORE_F32, st);
+            s_qkv = launch_gemm(dt, impl, ctx->a, ctx->wqkv[l], ctx->qkv, rows, qd + 2 * kvd, m.d_model, EPI_STORE_F32,
+                                ctx->slices, ctx->slice_cap, st);
         }
-        launch_rope_append(dt, ctx->qkv, row_slot, row_pos, ctx->d_slot_len, ctx->rope_cos, ctx->rope_sin, rows,
-                           m.n_q_heads, kv, l, ctx->q, st);
+        launch_rope_append(dt, s_qkv > 1 ? ctx->slices : ctx->qkv, s_qkv, row_slot, row_pos, ctx->d_slot_len,
+                           ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, st);
         if (ctx->mfma_attention()) {
             if (row_pos)
                 launch_attention_prefill_mfma(ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
@@ -189,40 +198,45 @@ void enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_
             else {
                 {
                     Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
-                    launch_attention_decode_mfma(ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l,
-                                                 max_ctx_now, ctx->attn_scratch, st);
+                    launch_attention_decode_mfma(ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
+                                                 ctx->attn_scratch, ctx->attn, st);
                 }
-                launch_attention_decode_merge(row_slot, ctx->d_slot_len, rows, m.n_q_heads, max_ctx_now,
+                launch_attention_decode_merge(row_slot, ctx->d_slot_len, rows, m.n_q_heads, n_splits,
                                               ctx->attn_scratch, ctx->attn, st);
             }
         } else {
             launch_attention_simt(dt, ctx->q, row_slot, row_pos, ctx->d_slot_len, rows, m.n_q_heads, kv, l, ctx->attn,
                                   st);
         }
+        int s_wo;
         {
             Timed t(ctx, PC_KERNEL_GEMM_WO, st);
-            launch_gemm(dt, impl, ctx->attn, ctx->wo[l], ctx->h, rows, m.d_model, qd, EPI_RESID_F32, st);
+            s_wo = launch_gemm(dt, impl, ctx->attn, ctx->wo[l], ctx->h, rows, m.d_model, qd, EPI_RESID_F32, ctx->slices,
+                               ctx->slice_cap, st);
         }
-        launch_rmsnorm(dt, ctx->h, nullptr, ctx->ffn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, st);
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->ffn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->slices, s_wo, st);
         {
             Timed t(ctx, PC_KERNEL_GEMM_GATE_UP, st);
-            launch_gemm(dt, impl, ctx->a, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU, st);
+            launch_gemm(dt, impl, ctx->a, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU, nullptr, 0, st);
         }
         {
             Timed t(ctx, PC_KERNEL_GEMM_DOWN, st);
-            launch_gemm(dt, impl, ctx->act, ctx->wdown[l], ctx->h, rows, m.d_model, m.d_ff, EPI_RESID_F32, st);
+            pending = launch_gemm(dt, impl, ctx->act, ctx->wdown[l], ctx->h, rows, m.d_model, m.d_ff, EPI_RESID_F32,
+                                  ctx->slices, ctx->slice_cap, st);
         }
     }
+    return pending;
 }
 
-void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits, int max_ctx_now, hipStream_t st) {
+void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits, hipStream_t st) {
     const pc_model_config &m = ctx->m;
     launch_embed(m.dtype, ctx->tok_embed, tokens_in, n, m.d_model, m.vocab, ctx->h, st);
-    enqueue_layers(ctx, n, ctx->d_dec_slot, nullptr, nullptr, nullptr, 0, 0, max_ctx_now, st);
-    launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, st);
+    const int pending = enqueue_layers(ctx, n, ctx->d_dec_slot, nullptr, nullptr, nullptr, 0, 0, st);
+    launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending, st);
     {
         Timed t(ctx, PC_KERNEL_GEMM_LM_HEAD, st);
-        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, st);
+        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, nullptr, 0,
+                    st);
     }
     launch_advance_len(ctx->d_slot_len, ctx->d_dec_slot, n, st);
 }
@@ -377,8 +391,9 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     TRY(dev_alloc((char **)&ctx->attn, R * qd * esz));
     TRY(dev_alloc((char **)&ctx->act, R * m.d_ff * esz));
     TRY(dev_alloc(&ctx->attn_scratch,
-                  attention_decode_scratch_floats(std::min<int>((int)R, cache->max_slots), m.n_q_heads, m.head_dim,
-                                                  cache->max_ctx)));
+                  attention_decode_scratch_floats(std::min<int>((int)R, cache->max_slots), m.n_q_heads, m.head_dim)));
+    ctx->slice_cap = (size_t)8 << 20;   // 32 MB
+    TRY(dev_alloc(&ctx->slices, ctx->slice_cap));
     TRY(dev_alloc(&ctx->d_meta, 2 * R + 3 * (size_t)cache->max_slots + 2 * (size_t)cache->max_slots + 16));
     TRY(dev_alloc(&ctx->d_dec_slot, (size_t)cache->max_slots));
     TRY_HIP(hipDeviceSynchronize());
@@ -516,10 +531,13 @@ pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int
         PC_HIP(hipMemcpyAsync(d_pslot, pslot.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
         PC_HIP(hipMemcpyAsync(d_last, last.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
         launch_embed(m.dtype, ctx->tok_embed, prompt_tokens + cu_lens[p0], rows, m.d_model, m.vocab, ctx->h, st);
-        enqueue_layers(ctx, rows, d_row_slot, d_row_pos, d_cu, d_pslot, np, max_len, 0, st);
-        launch_rmsnorm(m.dtype, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, st);
+        const int pending = enqueue_layers(ctx, rows, d_row_slot, d_row_pos, d_cu, d_pslot, np, max_len, st);
+        if (pending > 1)   // small chunk whose last projection was split: fold the slices into h first
+            launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->slices,
+                           pending, st);
+        launch_rmsnorm(m.dtype, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
         launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
-                    m.d_model, EPI_STORE_F32, st);
+                    m.d_model, EPI_STORE_F32, nullptr, 0, st);
         rc = check_launch();
         if (rc != PC_OK) return rc;
         // the metadata buffers are reused by the next chunk: pageable copies above were staged at call time
@@ -633,11 +651,10 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
         ctx->list_version++;
         PC_HIP(hipMemcpyAsync(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
     }
-    const int max_ctx_now = max_len + 1;
-    const int splits = (max_ctx_now + 511) / 512;
+    (void)max_len;
     if (ctx->use_graph && st != nullptr && ctx->time_class < 0) {   // the default stream cannot be captured
         const bool hit = ctx->exec && ctx->gkey.n == n && ctx->gkey.tokens == tokens_in && ctx->gkey.logits == logits &&
-                         ctx->gkey.stream == st && ctx->gkey.splits == splits &&
+                         ctx->gkey.stream == st &&
                          ctx->gkey.list_version == ctx->list_version;
         if (!hit) {
             if (ctx->exec) {
@@ -646,7 +663,7 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
             }
             hipGraph_t graph = nullptr;
             PC_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
-            enqueue_decode(ctx, tokens_in, n, logits, splits * 512, st);
+            enqueue_decode(ctx, tokens_in, n, logits, st);
             hipError_t e = hipStreamEndCapture(st, &graph);
             if (e != hipSuccess || !graph) PC_FAIL(PC_ERR_HIP, "pc_decode_step: stream capture failed: %s", hipGetErrorString(e));
             e = hipGraphInstantiate(&ctx->exec, graph, nullptr, nullptr, 0);
@@ -659,12 +676,11 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
             ctx->gkey.tokens = tokens_in;
             ctx->gkey.logits = logits;
             ctx->gkey.stream = st;
-            ctx->gkey.splits = splits;
             ctx->gkey.list_version = ctx->list_version;
         }
         PC_HIP(hipGraphLaunch(ctx->exec, st));
     } else {
-        enqueue_decode(ctx, tokens_in, n, logits, max_ctx_now, st);
+        enqueue_decode(ctx, tokens_in, n, logits, st);
         ctx->time_class = -1;   // timing covers one step
         pc_status rc = check_launch();
         if (rc != PC_OK) return rc;

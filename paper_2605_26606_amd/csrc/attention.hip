@@ -14,6 +14,8 @@
 // block, so both products read 16 contiguous bytes per lane straight from
 // global memory; no LDS staging is needed because every K/V byte is used by
 // exactly one wave.
+#include <algorithm>
+
 #include "pc_internal.h"
 
 namespace pc {
@@ -261,30 +263,46 @@ void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const 
 }
 
 // ---------------------------------------------------------------- decode
-static constexpr int SPLIT = 512;      // tokens per block
 static constexpr int DEC_WAVES = 4;
+static constexpr int ROUND = 32 * DEC_WAVES;   // tokens one block consumes per pass of its four waves
 
-// scratch layout per (row, q head, split): ml[2] = (max, sum), o[HD] (unnormalised)
-size_t attention_decode_scratch_floats(int rows, int hq, int hd, int max_ctx) {
-    size_t splits = (size_t)(max_ctx + SPLIT - 1) / SPLIT;
-    return (size_t)rows * hq * splits * (hd + 2);
+// Number of context splits: enough blocks to fill the chip, none when the batch alone does.
+int attention_decode_splits(int rows, int n_kv_heads, int max_ctx) {
+    const int blocks = rows * n_kv_heads;
+    int s = (512 + blocks - 1) / blocks;
+    s = std::min(s, std::max(1, (max_ctx + 2 * ROUND - 1) / (2 * ROUND)));
+    return std::max(1, std::min(s, 16));
 }
 
-// grid (splits, kv heads, rows), 4 waves per block; wave w takes the tiles w, w+4, ... of the split
+// scratch per (row, q head, split): (max, sum) and the unnormalised output [HD].
+// rows * splits(rows) never exceeds rows + 512 (splits > 1 only while rows * kv heads < 512).
+size_t attention_decode_scratch_floats(int max_rows, int hq, int hd) {
+    return (size_t)(max_rows + 512) * hq * (hd + 2);
+}
+
+// Every row cuts ITS context into n_splits equal pieces (rounded up to whole passes).
+__device__ inline int split_len(int ctx, int n_splits) {
+    return ((ctx + n_splits - 1) / n_splits + ROUND - 1) / ROUND * ROUND;
+}
+
+// grid (splits, kv heads, rows), 4 waves per block; wave w takes the tiles w, w+4, ... of the split.
+// DIRECT (one split): the block normalises and writes the attention output itself.
+template <bool DIRECT>
 __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t *__restrict__ q,
                                                                     const int32_t *__restrict__ row_slot,
                                                                     const int32_t *__restrict__ slot_len, int hq,
-                                                                    KvGeom kv, int layer, int max_splits,
-                                                                    float *__restrict__ part_ml,
-                                                                    float *__restrict__ part_o) {
+                                                                    KvGeom kv, int layer, float *__restrict__ part_ml,
+                                                                    float *__restrict__ part_o,
+                                                                    bf16_t *__restrict__ out) {
     __shared__ float sm[DEC_WAVES][16], sl[DEC_WAVES][16];
     __shared__ float so[DEC_WAVES][16][HD];
-    const int sp = blockIdx.x, kvh = blockIdx.y, r = blockIdx.z;
+    const int sp = blockIdx.x, n_splits = gridDim.x, kvh = blockIdx.y, r = blockIdx.z;
     const int slot = row_slot[r];
     const int ctx = slot_len[slot] + 1;
-    const int beg = sp * SPLIT;
+    const int len = split_len(ctx, n_splits);
+    const int beg = sp * len;
     if (beg >= ctx) return;
-    const int end = min(ctx, beg + SPLIT);
+    const int end = min(ctx, beg + len);
     const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE, i = lane % 16, g = lane / 16;
     const int rep = hq / kv.n_kv_heads;
     const bf16_t *head_base = (const bf16_t *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
@@ -300,7 +318,7 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
     AttnState st;
     state_init(st);
     const float scale_log2 = LOG2E / sqrtf((float)HD);
-    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, 32 * DEC_WAVES, end, ctx - 1,
+    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end, ctx - 1,
                  scale_log2, st);
     // ---- combine the four waves
     float l = st.l;
@@ -323,16 +341,29 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
         for (int nn = 0; nn < 8; ++nn) so[wave][col][16 * nn + i] = st.o[nn][v] * fw;
     }
     __syncthreads();
-    // thread t sums column t/16.. : 16 columns x 128 values = 2048 values over 256 threads
+    // 16 columns x 128 values over 256 threads; a thread's values all belong to one column per pass
     for (int e = tid; e < rep * HD; e += 256) {
         const int col = e / HD, c = e % HD;
         float v = 0.f;
 #pragma unroll
         for (int w = 0; w < DEC_WAVES; ++w) v += so[w][col][c];
-        const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * max_splits + sp;
-        part_o[idx * HD + c] = v;
+        if (DIRECT) {
+            float M = sm[0][col];
+#pragma unroll
+            for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+            float L = 0.f;
+#pragma unroll
+            for (int w = 0; w < DEC_WAVES; ++w) {
+                const float mw = sm[w][col];
+                L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
+            }
+            out[((int64_t)r * hq + kvh * rep + col) * HD + c] = f32_to_bf16(v / L);
+        } else {
+            const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * n_splits + sp;
+            part_o[idx * HD + c] = v;
+        }
     }
-    if (tid < rep) {
+    if (!DIRECT && tid < rep) {
         const int col = tid;
         float M = sm[0][col];
 #pragma unroll
@@ -343,7 +374,7 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
             const float mw = sm[w][col];
             L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
         }
-        const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * max_splits + sp;
+        const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * n_splits + sp;
         part_ml[2 * idx] = M;
         part_ml[2 * idx + 1] = L;
     }
@@ -352,13 +383,14 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
 // grid (q heads, rows), 128 threads: one per head_dim column
 __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32_t *__restrict__ row_slot,
                                                                      const int32_t *__restrict__ slot_len, int hq,
-                                                                     int max_splits, const float *__restrict__ part_ml,
+                                                                     int n_splits, const float *__restrict__ part_ml,
                                                                      const float *__restrict__ part_o,
                                                                      bf16_t *__restrict__ out) {
     const int head = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
     const int ctx = slot_len[row_slot[r]] + 1;
-    const int ns = (ctx + SPLIT - 1) / SPLIT;
-    const int64_t base = ((int64_t)r * hq + head) * max_splits;
+    const int len = split_len(ctx, n_splits);
+    const int ns = (ctx + len - 1) / len;            // the splits that found tokens
+    const int64_t base = ((int64_t)r * hq + head) * n_splits;
     const float scale_log2 = LOG2E / sqrtf((float)HD);
     float M = -INFINITY;
     for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[2 * (base + s)]);
@@ -372,24 +404,27 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
 }
 
 void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                  KvGeom kv, int layer, int max_ctx_now, float *scratch, hipStream_t s) {
+                                  KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
     if (rows <= 0) return;
-    const int max_splits = (max_ctx_now + SPLIT - 1) / SPLIT;
     float *part_ml = scratch;
-    float *part_o = scratch + (size_t)rows * hq * max_splits * 2;
-    dim3 grid(max_splits, kv.n_kv_heads, rows);
-    attention_decode_mfma_kernel<<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer, max_splits,
-                                                      part_ml, part_o);
+    float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
+    dim3 grid(n_splits, kv.n_kv_heads, rows);
+    if (n_splits == 1)
+        attention_decode_mfma_kernel<true><<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer,
+                                                                part_ml, part_o, (bf16_t *)out);
+    else
+        attention_decode_mfma_kernel<false><<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer,
+                                                                 part_ml, part_o, (bf16_t *)out);
 }
 
-void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int max_ctx_now,
+// only needed when n_splits > 1
+void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int n_splits,
                                    float *scratch, void *out, hipStream_t s) {
-    if (rows <= 0) return;
-    const int max_splits = (max_ctx_now + SPLIT - 1) / SPLIT;
+    if (rows <= 0 || n_splits <= 1) return;
     const float *part_ml = scratch;
-    const float *part_o = scratch + (size_t)rows * hq * max_splits * 2;
+    const float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
     dim3 mgrid(hq, rows);
-    attention_decode_merge_kernel<<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, max_splits, part_ml, part_o,
+    attention_decode_merge_kernel<<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
                                                         (bf16_t *)out);
 }
 

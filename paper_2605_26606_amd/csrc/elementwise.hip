@@ -36,42 +36,105 @@ void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows,
 
 // ------------------------------------------------------------------ RMSNorm
 // out = h * rsqrt(mean(h^2) + eps) * gain; one block per row, statistics in fp32.
-template <typename T>
-__global__ void rmsnorm_kernel(const float *__restrict__ h, const int32_t *__restrict__ src_row,
-                               const float *__restrict__ gain, int d, float eps, T *__restrict__ out) {
-    __shared__ float part[16];
-    int r = blockIdx.x;
-    const float *x = h + (int64_t)(src_row ? src_row[r] : r) * d;
-    float ss = 0.f;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) {
-        float v = x[i];
-        ss += v * v;
-    }
-    ss = wave_sum(ss);
-    int wid = threadIdx.x / WAVE, lane = threadIdx.x % WAVE, nw = blockDim.x / WAVE;
-    if (lane == 0) part[wid] = ss;
-    __syncthreads();
-    float tot = 0.f;
-    for (int i = 0; i < nw; ++i) tot += part[i];
-    float rs = 1.0f / sqrtf(tot / (float)d + eps);
-    T *o = out + (int64_t)r * d;
-    for (int i = threadIdx.x; i < d; i += blockDim.x) o[i] = from_f32<T>(x[i] * rs * gain[i]);
+// Pending split-K slices of the previous projection are folded into h first (slice order).
+// VEC4: d % 4 == 0 and d <= 4 * 256 * RMS_MAXV: the row lives in registers between the two passes.
+static constexpr int RMS_MAXV = 6;
+
+template <typename T> __device__ inline void store4(T *p, float4 v);
+template <> __device__ inline void store4<float>(float *p, float4 v) { *(float4 *)p = v; }
+template <> __device__ inline void store4<bf16_t>(bf16_t *p, float4 v) {
+    uint2 u;
+    u.x = (uint32_t)f32_to_bf16(v.x).x | ((uint32_t)f32_to_bf16(v.y).x << 16);
+    u.y = (uint32_t)f32_to_bf16(v.z).x | ((uint32_t)f32_to_bf16(v.w).x << 16);
+    *(uint2 *)p = u;
 }
 
-void launch_rmsnorm(int dtype, const float *h, const int32_t *src_row, const float *gain, int rows, int d, float eps,
-                    void *out, hipStream_t s) {
+template <typename T, bool VEC4>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const int32_t *__restrict__ src_row,
+                                                      const float *__restrict__ gain, int rows, int d, float eps,
+                                                      T *__restrict__ out, const float *__restrict__ slices, int S) {
+    __shared__ float part[4];
+    const int r = blockIdx.x, tid = threadIdx.x;
+    float *x = h + (int64_t)(src_row ? src_row[r] : r) * d;
+    float ss = 0.f;
+    float4 keep[RMS_MAXV];
+    if (VEC4) {
+        const int n4 = d / 4;
+#pragma unroll
+        for (int j = 0; j < RMS_MAXV; ++j) {
+            const int i = tid + 256 * j;
+            if (i < n4) {
+                float4 v = ((const float4 *)x)[i];
+                if (S > 1) {
+                    const float4 *sp = (const float4 *)(slices + (int64_t)r * d) + i;
+                    const int64_t zs = (int64_t)rows * d / 4;
+                    float4 add = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+                    for (int z = 0; z < S; ++z) {
+                        const float4 t = sp[z * zs];
+                        add.x += t.x; add.y += t.y; add.z += t.z; add.w += t.w;
+                    }
+                    v.x += add.x; v.y += add.y; v.z += add.z; v.w += add.w;
+                    ((float4 *)x)[i] = v;
+                }
+                keep[j] = v;
+                ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+            }
+        }
+    } else {
+        for (int i = tid; i < d; i += 256) {
+            float v = x[i];
+            if (S > 1) {
+                float add = 0.f;
+                for (int z = 0; z < S; ++z) add += slices[((int64_t)z * rows + r) * d + i];
+                v += add;
+                x[i] = v;
+            }
+            ss += v * v;
+        }
+    }
+    ss = wave_sum(ss);
+    if (tid % WAVE == 0) part[tid / WAVE] = ss;
+    __syncthreads();
+    const float tot = part[0] + part[1] + part[2] + part[3];
+    const float rs = 1.0f / sqrtf(tot / (float)d + eps);
+    T *o = out + (int64_t)r * d;
+    if (VEC4) {
+        const int n4 = d / 4;
+#pragma unroll
+        for (int j = 0; j < RMS_MAXV; ++j) {
+            const int i = tid + 256 * j;
+            if (i < n4) {
+                const float4 g = ((const float4 *)gain)[i];
+                float4 v = keep[j];
+                v.x = v.x * rs * g.x; v.y = v.y * rs * g.y; v.z = v.z * rs * g.z; v.w = v.w * rs * g.w;
+                store4<T>(o + 4 * i, v);
+            }
+        }
+    } else {
+        for (int i = tid; i < d; i += 256) o[i] = from_f32<T>(x[i] * rs * gain[i]);
+    }
+}
+
+void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *gain, int rows, int d, float eps,
+                    void *out, const float *slices, int S, hipStream_t s) {
     if (rows <= 0) return;
-    if (dtype == PC_DTYPE_F32)
-        rmsnorm_kernel<float><<<rows, 256, 0, s>>>(h, src_row, gain, d, eps, (float *)out);
-    else
-        rmsnorm_kernel<bf16_t><<<rows, 256, 0, s>>>(h, src_row, gain, d, eps, (bf16_t *)out);
+    const bool vec = (d % 4 == 0) && d <= 4 * 256 * RMS_MAXV;
+    if (dtype == PC_DTYPE_F32) {
+        if (vec) rmsnorm_kernel<float, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (float *)out, slices, S);
+        else rmsnorm_kernel<float, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (float *)out, slices, S);
+    } else {
+        if (vec) rmsnorm_kernel<bf16_t, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (bf16_t *)out, slices, S);
+        else rmsnorm_kernel<bf16_t, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (bf16_t *)out, slices, S);
+    }
 }
 
 // ------------------------------------------------------------------ RoPE + KV append
 // One block per row.  The pair (i, i + hd/2) of every q and k head turns by the
 // angle pos * theta^(-2i/hd) (cos/sin tables are built on the host in double).
 template <typename T>
-__global__ void rope_append_kernel(const float *__restrict__ qkv, const int32_t *__restrict__ row_slot,
+__global__ void rope_append_kernel(const float *__restrict__ qkv, int S, int rows,
+                                   const int32_t *__restrict__ row_slot,
                                    const int32_t *__restrict__ row_pos, const int32_t *__restrict__ slot_len,
                                    const float *__restrict__ rope_cos, const float *__restrict__ rope_sin, int hq,
                                    KvGeom kv, int layer, T *__restrict__ q_out) {
@@ -79,7 +142,14 @@ __global__ void rope_append_kernel(const float *__restrict__ qkv, const int32_t 
     const int hd = kv.head_dim, half = hd / 2, hkv = kv.n_kv_heads, bs = kv.block_size;
     const int slot = row_slot[r];
     const int pos = row_pos ? row_pos[r] : slot_len[slot];
-    const float *row = qkv + (int64_t)r * (hq + 2 * hkv) * hd;
+    const int width = (hq + 2 * hkv) * hd;
+    const float *row = qkv + (int64_t)r * width;
+    const int64_t zs = (int64_t)rows * width;   // distance between K slices
+    auto val = [&](int c) {
+        float v = row[c];
+        for (int z = 1; z < S; ++z) v += row[z * zs + c];
+        return v;
+    };
     const float *cs = rope_cos + (int64_t)pos * half;
     const float *sn = rope_sin + (int64_t)pos * half;
     const int blk = kv.block_table[(int64_t)slot * kv.max_blocks_per_slot + pos / bs];
@@ -89,39 +159,39 @@ __global__ void rope_append_kernel(const float *__restrict__ qkv, const int32_t 
     // q heads
     for (int i = threadIdx.x; i < hq * half; i += blockDim.x) {
         int head = i / half, j = i % half;
-        float x1 = row[head * hd + j], x2 = row[head * hd + j + half];
+        float x1 = val(head * hd + j), x2 = val(head * hd + j + half);
         float c = cs[j], sgn = sn[j];
         q_out[(int64_t)r * hq * hd + head * hd + j] = from_f32<T>(x1 * c - x2 * sgn);
         q_out[(int64_t)r * hq * hd + head * hd + j + half] = from_f32<T>(x2 * c + x1 * sgn);
     }
     // k heads -> K [tok][hd]
-    const float *krow = row + hq * hd;
+    const int koff = hq * hd;
     for (int i = threadIdx.x; i < hkv * half; i += blockDim.x) {
         int head = i / half, j = i % half;
-        float x1 = krow[head * hd + j], x2 = krow[head * hd + j + half];
+        float x1 = val(koff + head * hd + j), x2 = val(koff + head * hd + j + half);
         float c = cs[j], sgn = sn[j];
         T *kd = pool + (int64_t)head * kv.head_elems() + (int64_t)tin * hd;
         kd[j] = from_f32<T>(x1 * c - x2 * sgn);
         kd[j + half] = from_f32<T>(x2 * c + x1 * sgn);
     }
     // v heads -> V^T [hd][tok]
-    const float *vrow = krow + hkv * hd;
+    const int voff = koff + hkv * hd;
     for (int i = threadIdx.x; i < hkv * hd; i += blockDim.x) {
         int head = i / hd, j = i % hd;
         T *vd = pool + (int64_t)head * kv.head_elems() + (int64_t)bs * hd;
-        vd[(int64_t)j * bs + tin] = from_f32<T>(vrow[head * hd + j]);
+        vd[(int64_t)j * bs + tin] = from_f32<T>(val(voff + head * hd + j));
     }
 }
 
-void launch_rope_append(int dtype, const float *qkv, const int32_t *row_slot, const int32_t *row_pos,
+void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
                         KvGeom kv, int layer, void *q_out, hipStream_t s) {
     if (rows <= 0) return;
     if (dtype == PC_DTYPE_F32)
-        rope_append_kernel<float><<<rows, 256, 0, s>>>(qkv, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+        rope_append_kernel<float><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                        layer, (float *)q_out);
     else
-        rope_append_kernel<bf16_t><<<rows, 256, 0, s>>>(qkv, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+        rope_append_kernel<bf16_t><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                         layer, (bf16_t *)q_out);
 }
 

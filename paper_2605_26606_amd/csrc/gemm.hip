@@ -4,6 +4,8 @@
 //   gemm_simt   plain-ALU tiles, any dtype (the fp32 model path)
 //   gemm_mfma   bf16 on the matrix cores (v_mfma_f32_32x32x16_bf16), LDS
 //               double-buffered, one barrier per K tile
+#include <algorithm>
+
 #include "pc_internal.h"
 
 namespace pc {
@@ -94,87 +96,161 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
+static constexpr int N_XCD = 8;   // MI355X: 8 accelerator dies, each with its own L2; workgroup i runs on die i % 8
+
 // One 32x32x16 product per instruction.  Operand layout (wave of 64 lanes):
 //   a: lane l holds A[row = l%32][k = 8*(l/32) .. +7]
 //   b: lane l holds B[k = 8*(l/32) .. +7][col = l%32]   (= W[n = l%32][k...], contiguous in memory)
 //   d: lane l, element v holds D[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32]
-template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
-                                                        void *__restrict__ Cv, int M, int N, int K) {
+//
+// Work decomposition: a 1-D grid; workgroup id -> (m block, n block, K slice) such that the m blocks
+// that share a weight tile run on the same die back to back (the second one finds the tile in L2).
+// K slices (S > 1) write plain fp32 slices [S][M][N] to `Cv`; whoever consumes them adds them up in
+// slice order (no atomics, no fences: the kernel boundary orders the two).
+//
+// Data path: global memory -> LDS directly (global_load_lds_dwordx4, no register staging), NSTAGE
+// tiles deep, one barrier per K tile.  A wave-wide load lands as 1 KB of consecutive LDS (8 rows of
+// 64 k); to keep the 128-bit fragment reads conflict free without padding, the 16-byte chunk c of
+// row r is stored at chunk slot c ^ ((r >> 1) & 7) (the lane fetches the chunk its slot must hold).
+// K must be a multiple of 64 here.
+__device__ inline void wait_vmcnt(int) {}
+template <int N> __device__ inline void wait_vmcnt_le() {
+    // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = bits 15:14 | 3:0)
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int BM, int BN, int WM, int WN, int NSTAGE, int EPI>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
+                                                        void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
+                                                        int S, int plain) {
     constexpr int BK = 64;
-    constexpr int LDS_STRIDE = BK + 8;   // elements; 144-byte rows keep 128-bit LDS reads conflict-free
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_ITERS = BM / 32, W_ITERS = BN / 32;   // 256 threads move 32 rows of 64 k per pass
-    static_assert(WM * WN == 4, "four waves per block");
+    constexpr int NW = WM * WN;                           // waves per block
+    constexpr int A_ITERS = BM / (8 * NW), W_ITERS = BN / (8 * NW);   // the waves move 8*NW rows of 64 k per pass
+    constexpr int LOADS = A_ITERS + W_ITERS;              // load instructions per thread per K tile
+    constexpr int STAGE_ELEMS = (BM + BN) * BK;
+    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "whole passes");
     static_assert(EPI != EPI_SWIGLU || (BN / WN) == 64, "SwiGLU needs one 64-wide gate/up chunk per wave");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    bf16_t *As = (bf16_t *)smem_raw;                       // [2][BM][LDS_STRIDE]
-    bf16_t *Ws = As + 2 * BM * LDS_STRIDE;                 // [2][BN][LDS_STRIDE]
+    static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
+    extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+    bf16_t *smem = (bf16_t *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
+
+    // ---- which tile
+    const int id = blockIdx.x;
+    int bm, bn, z;
+    if (plain) {   // many row blocks (prefill): neighbours share the activation rows, plain order
+        bn = id % nb;
+        bm = id / nb;
+        z = 0;
+        if (bm >= mb) return;
+    } else {
+        const int die = id % N_XCD, j = id / N_XCD;
+        const int unit = (j / mb) * N_XCD + die;           // (n block, K slice) pair
+        if (unit >= nb * S) return;
+        bm = j % mb;
+        bn = unit % nb;
+        z = unit / nb;
+    }
+    const int m0 = bm * BM, n0 = bn * BN;
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / WN, wn = wave % WN;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
-    const int lrow = tid / 8, lchunk = tid % 8;            // global->LDS: row lrow (+32 per pass), 16-byte chunk lchunk
-    const int KT = (K + BK - 1) / BK;
+    const int KT = K / BK;
+    const int per = (KT + S - 1) / S;
+    const int kt0 = z * per, kt1 = min(KT, kt0 + per);
 
-    u32x4 ra[A_ITERS], rw[W_ITERS];
-    auto load_global = [&](int kt) {
-        const int k = kt * BK + lchunk * 8;
+    // ---- global -> LDS: in pass i this wave fills rows (4i + wave)*8 .. +7; lane -> (row, slot)
+    const int lr = lane / 8, slot = lane % 8;
+    const bf16_t *pa[A_ITERS], *pw[W_ITERS];
 #pragma unroll
-        for (int i = 0; i < A_ITERS; ++i) {
-            int r = m0 + lrow + 32 * i;
-            ra[i] = (r < M && k < K) ? *(const u32x4 *)(A + (int64_t)r * K + k) : (u32x4){0, 0, 0, 0};
-        }
+    for (int i = 0; i < A_ITERS; ++i) {
+        const int row = (NW * i + wave) * 8 + lr;
+        const int chunk = slot ^ ((row >> 1) & 7);
+        pa[i] = A + (int64_t)min(m0 + row, M - 1) * K + chunk * 8;   // rows past the end: clamped, results discarded
+    }
 #pragma unroll
-        for (int i = 0; i < W_ITERS; ++i) {
-            int r = n0 + lrow + 32 * i;
-            rw[i] = (r < N && k < K) ? *(const u32x4 *)(W + (int64_t)r * K + k) : (u32x4){0, 0, 0, 0};
-        }
-    };
-    auto store_lds = [&](int buf) {
+    for (int i = 0; i < W_ITERS; ++i) {
+        const int row = (NW * i + wave) * 8 + lr;
+        const int chunk = slot ^ ((row >> 1) & 7);
+        pw[i] = W + (int64_t)min(n0 + row, N - 1) * K + chunk * 8;
+    }
+    auto issue_tile = [&](int kt, int stage) {
+        const int koff = min(kt, kt1 - 1) * BK;            // past the end: a redundant reload, keeps the count constant
+        bf16_t *sa = smem + stage * STAGE_ELEMS;
+        bf16_t *sw = sa + BM * BK;
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i)
-            *(u32x4 *)(As + (buf * BM + lrow + 32 * i) * LDS_STRIDE + lchunk * 8) = ra[i];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + koff),
+                                             (__attribute__((address_space(3))) void *)(sa + (NW * i + wave) * 8 * BK), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < W_ITERS; ++i)
-            *(u32x4 *)(Ws + (buf * BN + lrow + 32 * i) * LDS_STRIDE + lchunk * 8) = rw[i];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pw[i] + koff),
+                                             (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * 8 * BK), 16, 0, 0);
     };
 
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int jj = 0; jj < TN; ++jj)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
 
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
+    // fragment addressing: lane (fr, fg) reads chunk 2*kk + fg of its row, stored at slot chunk ^ swz(row)
     const int fr = lane % 32, fg = lane / 32;
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT) load_global(kt + 1);
-        const bf16_t *as = As + (buf * BM + wm * (BM / WM) + fr) * LDS_STRIDE + fg * 8;
-        const bf16_t *ws = Ws + (buf * BN + wn * (BN / WN) + fr) * LDS_STRIDE + fg * 8;
+    int arow[TM], aswz[TM], wrow[TN], wswz[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        arow[i] = wm * (BM / WM) + i * 32 + fr;
+        aswz[i] = (arow[i] >> 1) & 7;
+    }
+#pragma unroll
+    for (int jj = 0; jj < TN; ++jj) {
+        wrow[jj] = wn * (BN / WN) + jj * 32 + fr;
+        wswz[jj] = (wrow[jj] >> 1) & 7;
+    }
+    auto load_frags = [&](const bf16_t *sa, const bf16_t *sw, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8 *)(sa + arow[i] * BK + (((2 * kk + fg) ^ aswz[i]) * 8));
+#pragma unroll
+        for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const bf16x8 *)(sw + wrow[jj] * BK + (((2 * kk + fg) ^ wswz[jj]) * 8));
+    };
+    auto compute = [&](int stage) {
+        const bf16_t *sa = smem + stage * STAGE_ELEMS;
+        const bf16_t *sw = sa + BM * BK;
+        bf16x8 fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
+        load_frags(sa, sw, 0, fa[0], fb[0]);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
-            bf16x8 fa[TM], fb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8 *)(as + i * 32 * LDS_STRIDE + kk * 16);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8 *)(ws + j * 32 * LDS_STRIDE + kk * 16);
+            if (kk + 1 < BK / 16) load_frags(sa, sw, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                for (int jj = 0; jj < TN; ++jj)
+                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj], 0, 0, 0);
         }
-        if (kt + 1 < KT) store_lds(buf ^ 1);
-        __syncthreads();
-    }
+    };
 
-    // epilogue
+    // tile kt lives in stage (kt - kt0) % NSTAGE; NSTAGE-1 tiles are in flight
+#pragma unroll
+    for (int s = 0; s < NSTAGE - 1; ++s) issue_tile(kt0 + s, s);
+    int stage = 0;
+    for (int kt = kt0; kt < kt1; ++kt) {
+        wait_vmcnt_le<(NSTAGE - 2) * LOADS>();             // this thread's loads of tile kt have landed
+        // ... and everybody's; tile kt-1 is fully consumed (its fragment reads were waited for before the
+        // matrix-core instructions that used them).  A bare barrier: __syncthreads() would add a fence that
+        // drains every load in flight.
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const int refill = (stage == 0) ? NSTAGE - 1 : stage - 1;
+        issue_tile(kt + NSTAGE - 1, refill);
+        compute(stage);
+        stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+    }
+    wait_vmcnt_le<0>();   // nothing may still be writing LDS when the block retires
+
+    // ---- epilogue
     const int col_l = lane % 32;
     const int row_l = 4 * (lane / 32);
 #pragma unroll
@@ -193,74 +269,120 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(const bf16_t *__restrict
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = n0 + wn * (BN / WN) + j * 32 + col_l;
+            for (int jj = 0; jj < TN; ++jj) {
+                const int col = n0 + wn * (BN / WN) + jj * 32 + col_l;
                 if (col >= N) continue;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     int row = rbase + 8 * (v / 4) + (v % 4);
                     if (row >= M) continue;
-                    if (EPI == EPI_STORE_F32) ((float *)Cv)[(int64_t)row * N + col] = acc[i][j][v];
-                    if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][j][v];
-                    if (EPI == EPI_STORE_T) ((bf16_t *)Cv)[(int64_t)row * N + col] = f32_to_bf16(acc[i][j][v]);
+                    if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
+                    if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
+                    if (EPI == EPI_STORE_T) ((bf16_t *)Cv)[(int64_t)row * N + col] = f32_to_bf16(acc[i][jj][v]);
                 }
             }
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN> struct MfmaCfg {
-    static constexpr size_t smem = (size_t)2 * (BM + BN) * (64 + 8) * sizeof(bf16_t);
+template <int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
+    static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
+    static constexpr bool swiglu_ok = (BN / WN == 64);
     template <int E> static void set_attr() {
-        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<BM, BN, WM, WN, E>,
+        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, E>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static void init() {
         set_attr<EPI_STORE_F32>();
         set_attr<EPI_RESID_F32>();
         set_attr<EPI_STORE_T>();
-        if constexpr (BN / WN == 64) set_attr<EPI_SWIGLU>();
+        if constexpr (swiglu_ok) set_attr<EPI_SWIGLU>();
     }
-    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, hipStream_t s) {
-        dim3 grid((N + BN - 1) / BN, (M + BM - 1) / BM);
+    // split > 1 only with EPI_STORE_F32, C then being the slice buffer [split][M][N]
+    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, int split, hipStream_t s) {
+        const int mb = (M + BM - 1) / BM, nb = (N + BN - 1) / BN;
+        const int units = nb * split;
+        const int plain = (split == 1 && mb > 4) ? 1 : 0;
+        const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<BM, BN, WM, WN, EPI_STORE_F32><<<grid, 256, smem, s>>>(a, w, C, M, N, K); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<BM, BN, WM, WN, EPI_RESID_F32><<<grid, 256, smem, s>>>(a, w, C, M, N, K); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
             case EPI_SWIGLU:
-                if constexpr (BN / WN == 64)
-                    gemm_mfma_kernel<BM, BN, WM, WN, EPI_SWIGLU><<<grid, 256, smem, s>>>(a, w, C, M, N, K);
+                if constexpr (swiglu_ok)
+                    gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
                 break;
-            default: gemm_mfma_kernel<BM, BN, WM, WN, EPI_STORE_T><<<grid, 256, smem, s>>>(a, w, C, M, N, K); break;
+            default: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
         }
+    }
+    // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
+    static int pick_split(int M, int N, int K, size_t slice_cap_floats, int want_blocks) {
+        const int64_t tiles = (int64_t)((N + BN - 1) / BN) * ((M + BM - 1) / BM);
+        const int KT = (K + 63) / 64;
+        int64_t split = (want_blocks + tiles / 2) / tiles;
+        split = std::min<int64_t>(split, KT / 4);
+        split = std::min<int64_t>(split, 8);
+        split = std::min<int64_t>(split, (int64_t)(slice_cap_floats / ((size_t)M * N)));
+        if (split < 2) return 1;
+        const int per = (KT + (int)split - 1) / (int)split;
+        return (KT + per - 1) / per;   // no empty slice
     }
 };
 
-typedef MfmaCfg<128, 128, 2, 2> CfgLarge;   // wave tile 64x64
-typedef MfmaCfg<128, 64, 4, 1> CfgSkinny;   // wave tile 32x64: more blocks when M is small
+typedef MfmaCfg<128, 128, 2, 2, 4> CfgLarge;   // wave tile 64x64, 128 KB of LDS: one block per CU, 3 tiles in flight
+typedef MfmaCfg<64, 64, 2, 2, 4> CfgSmall;     // wave tile 32x32: many blocks for the small projections
+typedef MfmaCfg<256, 128, 4, 2, 3> CfgTall;     // 8 waves, wave tile 64x64, 144 KB of LDS: every decode row in one block
 
 void gemm_init() {
     CfgLarge::init();
-    CfgSkinny::init();
+    CfgSmall::init();
+    CfgTall::init();
 }
 
-static void gemm_mfma(const void *A, const void *W, void *C, int M, int N, int K, int epi, hipStream_t s) {
-    if (M > 512)
-        CfgLarge::run(A, W, C, M, N, K, epi, s);
-    else
-        CfgSkinny::run(A, W, C, M, N, K, epi, s);
-}
-
-void launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                 hipStream_t s) {
-    if (M <= 0 || N <= 0) return;
+int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
+                float *slices, size_t slice_cap_floats, hipStream_t s) {
+    if (M <= 0 || N <= 0) return 1;
     if (dtype == PC_DTYPE_F32) {
         gemm_simt<float>(A, W, C, M, N, K, epi, s);
-    } else if (impl == 0 || (K % 8) != 0) {
-        gemm_simt<bf16_t>(A, W, C, M, N, K, epi, s);
-    } else {
-        gemm_mfma(A, W, C, M, N, K, epi, s);
+        return 1;
     }
+    if (impl == 0 || (K % 64) != 0) {
+        gemm_simt<bf16_t>(A, W, C, M, N, K, epi, s);
+        return 1;
+    }
+    if (M > 512) {   // prefill: plenty of tiles
+        CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
+        return 1;
+    }
+    // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
+    const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
+    const int64_t large_tiles = (int64_t)((N + 127) / 128) * ((M + 127) / 128);
+    const bool big = epi == EPI_SWIGLU || large_tiles >= 192 || (int64_t)N * K >= (int64_t)8 << 20;
+    if (big && M > 128 && (N + 127) / 128 >= 96) {   // all rows in one 256-row block: a weight tile is fetched once
+        const int split = can_split ? CfgTall::pick_split(M, N, K, slice_cap_floats, 192) : 1;
+        if (split > 1) {
+            CfgTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+            return split;
+        }
+        CfgTall::run(A, W, C, M, N, K, epi, 1, s);
+        return 1;
+    }
+    if (big) {
+        const int split = can_split ? CfgLarge::pick_split(M, N, K, slice_cap_floats, 192) : 1;
+        if (split > 1) {
+            CfgLarge::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+            return split;
+        }
+        CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
+        return 1;
+    }
+    const int split = can_split ? CfgSmall::pick_split(M, N, K, slice_cap_floats, 128) : 1;
+    if (split > 1) {
+        CfgSmall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+        return split;
+    }
+    CfgSmall::run(A, W, C, M, N, K, epi, 1, s);
+    return 1;
 }
 
 }  // namespace pc

@@ -82,16 +82,23 @@ enum Epilogue {
 // (each validates nothing: callers pass shapes that the context has checked)
 void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows, int d, int vocab, float *h,
                   hipStream_t s);
-// out[r] = norm(h[src_row ? src_row[r] : r]) * gain, in the model dtype
-void launch_rmsnorm(int dtype, const float *h, const int32_t *src_row, const float *gain, int rows, int d,
-                    float eps, void *out, hipStream_t s);
+// out[r] = norm(h[src_row ? src_row[r] : r]) * gain, in the model dtype.  With S > 1 slices
+// [S][rows][d] pending (a split-K product not yet added to the residual stream), h[r] += their sum first
+// (written back); src_row must be NULL then.
+void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *gain, int rows, int d, float eps,
+                    void *out, const float *slices, int S, hipStream_t s);
 // C = A[M,K] * W[N,K]^T with the given epilogue.  impl 0: plain ALU, 1: matrix cores (bf16 only)
 void gemm_init();   // once per process: raises the dynamic-LDS limit of the matrix-core kernels
-void launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                 hipStream_t s);
+// Returns the number of K slices S the product was cut into.  S == 1: C holds the finished result.
+// S > 1 (only when `slices` is given, for EPI_STORE_F32 / EPI_RESID_F32 at decode sizes): C is untouched
+// and `slices` holds S fp32 partial products [S][M][N]; the consumer adds them in slice order (and, for
+// EPI_RESID_F32, adds that sum to the residual stream).
+int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
+                float *slices, size_t slice_cap_floats, hipStream_t s);
 // Rotates q and k at each row's position, writes q (model dtype) and appends k, v to the cache.
-//   qkv fp32 [rows, (hq+2hkv)*hd]; row_slot [rows]; row_pos [rows] or NULL (then pos = slot_len[slot])
-void launch_rope_append(int dtype, const float *qkv, const int32_t *row_slot, const int32_t *row_pos,
+//   qkv fp32 [S][rows, (hq+2hkv)*hd] (S >= 1 K slices, summed here); row_slot [rows];
+//   row_pos [rows] or NULL (then pos = slot_len[slot])
+void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
                         KvGeom kv, int layer, void *q_out, hipStream_t s);
 // Attention of each row's query heads over its slot's cache, positions 0..pos (plain ALU).
@@ -101,12 +108,14 @@ void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, co
 // Matrix-core attention (bf16).  Prefill: rows of each prompt are contiguous and start at position 0.
 void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
                                    int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s);
-// Decode: one query row per sequence; split-KV with a merge pass.  scratch: fp32 workspace.
+// Decode: one query row per sequence.  n_splits = attention_decode_splits(...): with one split the
+// kernel writes `out` itself, otherwise it leaves partial results in `scratch` for the merge pass.
+int attention_decode_splits(int rows, int n_kv_heads, int max_ctx);
 void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                  KvGeom kv, int layer, int max_ctx_now, float *scratch, hipStream_t s);
-void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int max_ctx_now,
+                                  KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s);
+void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int n_splits,
                                    float *scratch, void *out, hipStream_t s);
-size_t attention_decode_scratch_floats(int rows, int hq, int hd, int max_ctx);
+size_t attention_decode_scratch_floats(int max_rows, int hq, int hd);
 
 void launch_advance_len(int32_t *slot_len, const int32_t *row_slot, int rows, hipStream_t s);
 void launch_copy_block(int dtype, KvGeom kv, int n_layers, const int32_t *src_dst_pairs, int n_pairs, hipStream_t s);
