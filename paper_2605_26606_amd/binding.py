@@ -33,7 +33,7 @@ class PcError(RuntimeError):
 
 class _ModelConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ff", "vocab")] \
-        + [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32)]
+        + [("rms_eps", C.c_float), ("rope_theta", C.c_float), ("dtype", C.c_int32), ("act_dtype", C.c_int32)]
 
 
 class _Weights(C.Structure):
@@ -119,13 +119,14 @@ class Context:
     workloads.make_weights produces them; they are kept alive here."""
 
     def __init__(self, model, weights: dict, block_size: int = 64, kv_pool_bytes: int = 1 << 30,
-                 max_slots: int = 1024, max_ctx: int = 2048, max_batch_rows: int = 4096):
+                 max_slots: int = 1024, max_ctx: int = 2048, max_batch_rows: int = 4096, act_dtype: str = "default"):
         lib = library()
         self.model = model
         self.vocab = int(model.vocab)
         self._weights = weights
         mc = _ModelConfig(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
-                          model.d_ff, model.vocab, model.rms_eps, model.rope_theta, _DTYPES[model.dtype])
+                          model.d_ff, model.vocab, model.rms_eps, model.rope_theta, _DTYPES[model.dtype],
+                          {"default": 0, "bf16": 1, "f16": 2}[act_dtype])
         tdt = torch.float32 if model.dtype == "fp32" else torch.bfloat16
         L = model.n_layers
 

@@ -37,6 +37,8 @@ struct pc_ctx {
     pc_model_config m;
     pc_cache_config c;
     int device = 0;
+    int kd = KD_F32;      // kernel dtype of activations, KV cache and weight copies
+    void *lm_head_copy = nullptr;   // half copy of lm_head (KD_F16)
     size_t esz = 2;
     // weights (library-owned fused copies, except embed / lm_head / final_norm)
     const void *tok_embed = nullptr, *lm_head = nullptr;
@@ -89,7 +91,7 @@ struct pc_ctx {
         g.block_table = d_block_table;
         return g;
     }
-    int impl() const { return (m.dtype == PC_DTYPE_BF16 && !force_simt) ? 1 : 0; }
+    int impl() const { return (kd != KD_F32 && !force_simt) ? 1 : 0; }
     bool mfma_attention() const { return impl() == 1 && m.head_dim == 128 && (m.n_q_heads / m.n_kv_heads) <= 16; }
 };
 
@@ -114,7 +116,7 @@ void free_all(pc_ctx *ctx) {
     for (auto p : ctx->ffn_norm) fr(p);
     fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
     fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
-    fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices);
+    fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices); fr(ctx->lm_head_copy);
 }
 
 // uploads rows [s0, s1] of the host block table and slot lengths
@@ -175,7 +177,7 @@ struct Timed {
 int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t *row_pos, const int32_t *cu_rows,
                    const int32_t *prompt_slot, int n_prompts, int max_len, hipStream_t st) {
     const pc_model_config &m = ctx->m;
-    const int dt = m.dtype, impl = ctx->impl();
+    const int dt = ctx->kd, impl = ctx->impl();
     const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     const KvGeom kv = ctx->geom();
     const int n_splits = attention_decode_splits(rows, m.n_kv_heads, ctx->c.max_ctx);
@@ -193,15 +195,15 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
                            ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, st);
         if (ctx->mfma_attention()) {
             if (row_pos)
-                launch_attention_prefill_mfma(ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
+                launch_attention_prefill_mfma(dt, ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
                                               ctx->attn, st);
             else {
                 {
                     Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
-                    launch_attention_decode_mfma(ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
+                    launch_attention_decode_mfma(dt, ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
                                                  ctx->attn_scratch, ctx->attn, st);
                 }
-                launch_attention_decode_merge(row_slot, ctx->d_slot_len, rows, m.n_q_heads, n_splits,
+                launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, n_splits,
                                               ctx->attn_scratch, ctx->attn, st);
             }
         } else {
@@ -230,12 +232,12 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
 
 void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits, hipStream_t st) {
     const pc_model_config &m = ctx->m;
-    launch_embed(m.dtype, ctx->tok_embed, tokens_in, n, m.d_model, m.vocab, ctx->h, st);
+    launch_embed(ctx->kd, ctx->tok_embed, tokens_in, n, m.d_model, m.vocab, ctx->h, st);
     const int pending = enqueue_layers(ctx, n, ctx->d_dec_slot, nullptr, nullptr, nullptr, 0, 0, st);
-    launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending, st);
+    launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending, st);
     {
         Timed t(ctx, PC_KERNEL_GEMM_LM_HEAD, st);
-        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, nullptr, 0,
+        launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, nullptr, 0,
                     st);
     }
     launch_advance_len(ctx->d_slot_len, ctx->d_dec_slot, n, st);
@@ -261,6 +263,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
         m.vocab <= 0 || !(m.rms_eps >= 0.f) || !(m.rope_theta > 0.f))
         PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: non-positive model dimension");
     if (m.dtype != PC_DTYPE_F32 && m.dtype != PC_DTYPE_BF16) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: unknown dtype");
+    if (m.act_dtype < PC_ACT_DEFAULT || m.act_dtype > PC_ACT_F16) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: unknown act_dtype");
     if (m.n_q_heads % m.n_kv_heads) PC_FAIL(PC_ERR_INVALID_ARG, "pc_create: n_q_heads not a multiple of n_kv_heads");
     if (m.head_dim % 2 || m.head_dim > 256) PC_FAIL(PC_ERR_UNSUPPORTED, "pc_create: head_dim must be even and <= 256");
     if (m.d_ff % 32) PC_FAIL(PC_ERR_UNSUPPORTED, "pc_create: d_ff must be a multiple of 32");
@@ -281,6 +284,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     ctx->m = m;
     ctx->c = *cache;
     ctx->esz = (m.dtype == PC_DTYPE_F32) ? 4 : 2;
+    ctx->kd = (m.dtype == PC_DTYPE_F32) ? KD_F32 : (m.act_dtype == PC_ACT_BF16 ? KD_BF16 : KD_F16);
     pc_status rc = PC_OK;
 #define TRY(expr)                 \
     do {                          \
@@ -316,24 +320,30 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
         float *g;
         TRY(dev_alloc((char **)&p, (size_t)(qd + 2 * kvd) * m.d_model * esz));
         ctx->wqkv.push_back(p);
-        launch_pack_rows(m.dtype, w->wq[l], p, qd, m.d_model, 0, st);
-        launch_pack_rows(m.dtype, w->wk[l], p, kvd, m.d_model, qd, st);
-        launch_pack_rows(m.dtype, w->wv[l], p, kvd, m.d_model, qd + kvd, st);
+        launch_pack_rows(ctx->kd, w->wq[l], p, qd, m.d_model, 0, st);
+        launch_pack_rows(ctx->kd, w->wk[l], p, kvd, m.d_model, qd, st);
+        launch_pack_rows(ctx->kd, w->wv[l], p, kvd, m.d_model, qd + kvd, st);
         TRY(dev_alloc((char **)&p, (size_t)m.d_model * qd * esz));
         ctx->wo.push_back(p);
-        TRY_HIP(hipMemcpyAsync(p, w->wo[l], (size_t)m.d_model * qd * esz, hipMemcpyDeviceToDevice, st));
+        launch_pack_rows(ctx->kd, w->wo[l], p, m.d_model, qd, 0, st);
         TRY(dev_alloc((char **)&p, (size_t)2 * m.d_ff * m.d_model * esz));
         ctx->wgu.push_back(p);
-        launch_pack_gate_up(m.dtype, w->w_gate[l], w->w_up[l], p, m.d_ff, m.d_model, st);
+        launch_pack_gate_up(ctx->kd, w->w_gate[l], w->w_up[l], p, m.d_ff, m.d_model, st);
         TRY(dev_alloc((char **)&p, (size_t)m.d_model * m.d_ff * esz));
         ctx->wdown.push_back(p);
-        TRY_HIP(hipMemcpyAsync(p, w->w_down[l], (size_t)m.d_model * m.d_ff * esz, hipMemcpyDeviceToDevice, st));
+        launch_pack_rows(ctx->kd, w->w_down[l], p, m.d_model, m.d_ff, 0, st);
         TRY(dev_alloc(&g, (size_t)m.d_model));
         ctx->attn_norm.push_back(g);
         TRY_HIP(hipMemcpyAsync(g, w->attn_norm[l], (size_t)m.d_model * 4, hipMemcpyDeviceToDevice, st));
         TRY(dev_alloc(&g, (size_t)m.d_model));
         ctx->ffn_norm.push_back(g);
         TRY_HIP(hipMemcpyAsync(g, w->ffn_norm[l], (size_t)m.d_model * 4, hipMemcpyDeviceToDevice, st));
+    }
+
+    if (ctx->kd == KD_F16) {   // the output projection is read through a half copy
+        TRY(dev_alloc((char **)&ctx->lm_head_copy, (size_t)m.vocab * m.d_model * esz));
+        launch_pack_rows(ctx->kd, w->lm_head, ctx->lm_head_copy, m.vocab, m.d_model, 0, st);
+        ctx->lm_head = ctx->lm_head_copy;
     }
 
     // ---- KV pool
@@ -530,13 +540,13 @@ pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int
         PC_HIP(hipMemcpyAsync(d_cu, cu.data(), (size_t)(np + 1) * 4, hipMemcpyHostToDevice, st));
         PC_HIP(hipMemcpyAsync(d_pslot, pslot.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
         PC_HIP(hipMemcpyAsync(d_last, last.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
-        launch_embed(m.dtype, ctx->tok_embed, prompt_tokens + cu_lens[p0], rows, m.d_model, m.vocab, ctx->h, st);
+        launch_embed(ctx->kd, ctx->tok_embed, prompt_tokens + cu_lens[p0], rows, m.d_model, m.vocab, ctx->h, st);
         const int pending = enqueue_layers(ctx, rows, d_row_slot, d_row_pos, d_cu, d_pslot, np, max_len, st);
         if (pending > 1)   // small chunk whose last projection was split: fold the slices into h first
-            launch_rmsnorm(m.dtype, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->slices,
+            launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->slices,
                            pending, st);
-        launch_rmsnorm(m.dtype, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
-        launch_gemm(m.dtype, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
+        launch_rmsnorm(ctx->kd, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
+        launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
                     m.d_model, EPI_STORE_F32, nullptr, 0, st);
         rc = check_launch();
         if (rc != PC_OK) return rc;
@@ -604,7 +614,7 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
     if (!pairs.empty()) {
         int32_t *d_pairs = ctx->d_meta + 2 * (size_t)ctx->c.max_batch_rows + 3 * (size_t)ctx->c.max_slots + 8;
         PC_HIP(hipMemcpyAsync(d_pairs, pairs.data(), pairs.size() * 4, hipMemcpyHostToDevice, st));
-        launch_copy_block(ctx->m.dtype, ctx->geom(), ctx->m.n_layers, d_pairs, (int)pairs.size() / 2, st);
+        launch_copy_block(ctx->kd, ctx->geom(), ctx->m.n_layers, d_pairs, (int)pairs.size() / 2, st);
         rc = check_launch();
     }
     return rc;

@@ -101,19 +101,21 @@ void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, co
                            hipStream_t s) {
     if (rows <= 0) return;
     dim3 grid(hq, rows);
-    if (dtype == PC_DTYPE_F32)
+    if (dtype == KD_F32)
         attention_simt_kernel<float><<<grid, 64, 0, s>>>((const float *)q, row_slot, row_pos, slot_len, hq, kv, layer,
                                                          (float *)out);
-    else
+    else if (dtype == KD_BF16)
         attention_simt_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, row_slot, row_pos, slot_len, hq, kv,
                                                           layer, (bf16_t *)out);
+    else
+        attention_simt_kernel<f16_t><<<grid, 64, 0, s>>>((const f16_t *)q, row_slot, row_pos, slot_len, hq, kv, layer,
+                                                         (f16_t *)out);
 }
 
 // =====================================================================================
 // matrix-core attention, head_dim = 128
 // =====================================================================================
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef f32x4_t f32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 static constexpr int HD = 128;
@@ -127,27 +129,27 @@ struct AttnState {
     f32x4 o[8];     // O[column 4g+v][16*nn + i]
 };
 
-__device__ inline bf16x8 ld_frag(const bf16_t *p) {
+template <typename T> __device__ inline typename Mma<T>::frag ld_frag(const T *p) {
     u32x4 t = *(const u32x4 *)p;
-    return __builtin_bit_cast(bf16x8, t);
+    return __builtin_bit_cast(typename Mma<T>::frag, t);
 }
-
-__device__ inline uint32_t pack_bf16x2(float a, float b) {
-    return (uint32_t)f32_to_bf16(a).x | ((uint32_t)f32_to_bf16(b).x << 16);
+template <typename T> __device__ inline typename Mma<T>::frag zero_frag() {
+    return __builtin_bit_cast(typename Mma<T>::frag, (u32x4){0, 0, 0, 0});
 }
 
 // Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end.
 // Tokens > col_limit (this lane's column) or >= tok_end are masked.
-__device__ inline void attend_tiles(const bf16_t *__restrict__ head_base, int64_t block_elems,
-                                    const int32_t *__restrict__ table, int bs, const bf16x8 (&qf)[4], int tile_begin,
+template <typename T>
+__device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t block_elems,
+                                    const int32_t *__restrict__ table, int bs, const typename Mma<T>::frag (&qf)[4], int tile_begin,
                                     int tile_step, int tok_end, int col_limit, float scale_log2, AttnState &st) {
     const int lane = threadIdx.x % WAVE, i = lane % 16, g = lane / 16;
     const int krow = 8 * (i / 4) + (i % 4);   // tile u reads token krow + 4u: lane (column, g) then owns tokens 8g..8g+7
     for (int t0 = tile_begin; t0 < tok_end; t0 += tile_step) {
         const int tin = t0 % bs;
-        const bf16_t *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
-        const bf16_t *vb = kb + (int64_t)bs * HD;
-        bf16x8 ka[2][4], vf[8];
+        const T *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
+        const T *vb = kb + (int64_t)bs * HD;
+        typename Mma<T>::frag ka[2][4], vf[8];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -160,7 +162,7 @@ __device__ inline void attend_tiles(const bf16_t *__restrict__ head_base, int64_
         for (int u = 0; u < 2; ++u) {
             s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) s[u] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[u][kk], qf[kk], s[u], 0, 0, 0);
+            for (int kk = 0; kk < 4; ++kk) s[u] = Mma<T>::m16(ka[u][kk], qf[kk], s[u]);
         }
         // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
         float mx = -INFINITY;
@@ -191,14 +193,14 @@ __device__ inline void attend_tiles(const bf16_t *__restrict__ head_base, int64_
         float c4[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
-        u32x4 pw = {pack_bf16x2(p[0][0], p[0][1]), pack_bf16x2(p[0][2], p[0][3]), pack_bf16x2(p[1][0], p[1][1]),
-                    pack_bf16x2(p[1][2], p[1][3])};
-        const bf16x8 pa = __builtin_bit_cast(bf16x8, pw);
+        u32x4 pw = {pack2<T>(p[0][0], p[0][1]), pack2<T>(p[0][2], p[0][3]), pack2<T>(p[1][0], p[1][1]),
+                    pack2<T>(p[1][2], p[1][3])};
+        const typename Mma<T>::frag pa = __builtin_bit_cast(typename Mma<T>::frag, pw);
 #pragma unroll
         for (int nn = 0; nn < 8; ++nn) {
 #pragma unroll
             for (int v = 0; v < 4; ++v) st.o[nn][v] *= c4[v];
-            st.o[nn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, vf[nn], st.o[nn], 0, 0, 0);
+            st.o[nn] = Mma<T>::m16(pa, vf[nn], st.o[nn]);
         }
     }
 }
@@ -212,26 +214,27 @@ __device__ inline void state_init(AttnState &st) {
 
 // ---------------------------------------------------------------- prefill
 // grid (query tiles of 16, q heads, prompts), one wave per block
-__global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const bf16_t *__restrict__ q,
+template <typename T>
+__global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__restrict__ q,
                                                                     const int32_t *__restrict__ cu_rows,
                                                                     const int32_t *__restrict__ prompt_slot, int hq,
-                                                                    KvGeom kv, int layer, bf16_t *__restrict__ out) {
+                                                                    KvGeom kv, int layer, T *__restrict__ out) {
     const int p = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 16;
     const int row0 = cu_rows[p], len = cu_rows[p + 1] - row0;
     if (q0 >= len) return;
     const int lane = threadIdx.x, i = lane % 16, g = lane / 16;
     const int slot = prompt_slot[p];
     const int kvh = head / (hq / kv.n_kv_heads);
-    const bf16_t *head_base = (const bf16_t *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
+    const T *head_base = (const T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
     const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
     const bool col_ok = (q0 + i) < len;
-    bf16x8 qf[4];
+    typename Mma<T>::frag qf[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         if (col_ok)
             qf[kk] = ld_frag(q + ((int64_t)(row0 + q0 + i) * hq + head) * HD + 32 * kk + 8 * g);
         else
-            qf[kk] = __builtin_bit_cast(bf16x8, (u32x4){0, 0, 0, 0});
+            qf[kk] = zero_frag<T>();
     }
     AttnState st;
     state_init(st);
@@ -247,19 +250,23 @@ __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const bf16_t
         const float lc = __shfl(l, col, WAVE);
         if (q0 + col < len) {
             const float inv = 1.0f / lc;
-            bf16_t *o = out + ((int64_t)(row0 + q0 + col) * hq + head) * HD;
+            T *o = out + ((int64_t)(row0 + q0 + col) * hq + head) * HD;
 #pragma unroll
-            for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = f32_to_bf16(st.o[nn][v] * inv);
+            for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = from_f32<T>(st.o[nn][v] * inv);
         }
     }
 }
 
-void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
-                                   int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
+                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
     if (n_prompts <= 0 || max_len <= 0) return;
     dim3 grid((max_len + 15) / 16, hq, n_prompts);
-    attention_prefill_mfma_kernel<<<grid, 64, 0, s>>>((const bf16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
-                                                      (bf16_t *)out);
+    if (dtype == KD_BF16)
+        attention_prefill_mfma_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
+                                                                  (bf16_t *)out);
+    else
+        attention_prefill_mfma_kernel<f16_t><<<grid, 64, 0, s>>>((const f16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
+                                                                 (f16_t *)out);
 }
 
 // ---------------------------------------------------------------- decode
@@ -287,13 +294,13 @@ __device__ inline int split_len(int ctx, int n_splits) {
 
 // grid (splits, kv heads, rows), 4 waves per block; wave w takes the tiles w, w+4, ... of the split.
 // DIRECT (one split): the block normalises and writes the attention output itself.
-template <bool DIRECT>
-__global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t *__restrict__ q,
+template <typename T, bool DIRECT>
+__global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__restrict__ q,
                                                                     const int32_t *__restrict__ row_slot,
                                                                     const int32_t *__restrict__ slot_len, int hq,
                                                                     KvGeom kv, int layer, float *__restrict__ part_ml,
                                                                     float *__restrict__ part_o,
-                                                                    bf16_t *__restrict__ out) {
+                                                                    T *__restrict__ out) {
     __shared__ float sm[DEC_WAVES][16], sl[DEC_WAVES][16];
     __shared__ float so[DEC_WAVES][16][HD];
     const int sp = blockIdx.x, n_splits = gridDim.x, kvh = blockIdx.y, r = blockIdx.z;
@@ -305,15 +312,15 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
     const int end = min(ctx, beg + len);
     const int tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE, i = lane % 16, g = lane / 16;
     const int rep = hq / kv.n_kv_heads;
-    const bf16_t *head_base = (const bf16_t *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
+    const T *head_base = (const T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
     const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
-    bf16x8 qf[4];
+    typename Mma<T>::frag qf[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         if (i < rep)
             qf[kk] = ld_frag(q + ((int64_t)r * hq + kvh * rep + i) * HD + 32 * kk + 8 * g);
         else
-            qf[kk] = __builtin_bit_cast(bf16x8, (u32x4){0, 0, 0, 0});
+            qf[kk] = zero_frag<T>();
     }
     AttnState st;
     state_init(st);
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
                 const float mw = sm[w][col];
                 L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
             }
-            out[((int64_t)r * hq + kvh * rep + col) * HD + c] = f32_to_bf16(v / L);
+            out[((int64_t)r * hq + kvh * rep + col) * HD + c] = from_f32<T>(v / L);
         } else {
             const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * n_splits + sp;
             part_o[idx * HD + c] = v;
@@ -381,11 +388,12 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const bf16_t
 }
 
 // grid (q heads, rows), 128 threads: one per head_dim column
+template <typename T>
 __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32_t *__restrict__ row_slot,
                                                                      const int32_t *__restrict__ slot_len, int hq,
                                                                      int n_splits, const float *__restrict__ part_ml,
                                                                      const float *__restrict__ part_o,
-                                                                     bf16_t *__restrict__ out) {
+                                                                     T *__restrict__ out) {
     const int head = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
     const int ctx = slot_len[row_slot[r]] + 1;
     const int len = split_len(ctx, n_splits);
@@ -400,32 +408,43 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
         L += f * part_ml[2 * (base + s) + 1];
         acc += f * part_o[(base + s) * HD + c];
     }
-    out[((int64_t)r * hq + head) * HD + c] = f32_to_bf16(acc / L);
+    out[((int64_t)r * hq + head) * HD + c] = from_f32<T>(acc / L);
 }
 
-void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                  KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
-    if (rows <= 0) return;
+template <typename T>
+static void decode_launch(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
+                          int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
     float *part_ml = scratch;
     float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
     dim3 grid(n_splits, kv.n_kv_heads, rows);
     if (n_splits == 1)
-        attention_decode_mfma_kernel<true><<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer,
-                                                                part_ml, part_o, (bf16_t *)out);
+        attention_decode_mfma_kernel<T, true><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer,
+                                                                   part_ml, part_o, (T *)out);
     else
-        attention_decode_mfma_kernel<false><<<grid, 256, 0, s>>>((const bf16_t *)q, row_slot, slot_len, hq, kv, layer,
-                                                                 part_ml, part_o, (bf16_t *)out);
+        attention_decode_mfma_kernel<T, false><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer,
+                                                                    part_ml, part_o, (T *)out);
+}
+
+void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
+                                  int hq, KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
+    if (rows <= 0) return;
+    if (dtype == KD_BF16) decode_launch<bf16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, scratch, out, s);
+    else decode_launch<f16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, scratch, out, s);
 }
 
 // only needed when n_splits > 1
-void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int n_splits,
-                                   float *scratch, void *out, hipStream_t s) {
+void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
+                                   int n_splits, float *scratch, void *out, hipStream_t s) {
     if (rows <= 0 || n_splits <= 1) return;
     const float *part_ml = scratch;
     const float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
     dim3 mgrid(hq, rows);
-    attention_decode_merge_kernel<<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
-                                                        (bf16_t *)out);
+    if (dtype == KD_BF16)
+        attention_decode_merge_kernel<bf16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
+                                                                    (bf16_t *)out);
+    else
+        attention_decode_merge_kernel<f16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
+                                                                   (f16_t *)out);
 }
 
 }  // namespace pc

@@ -28,7 +28,7 @@ __global__ void embed_kernel(const T *__restrict__ table, const int32_t *__restr
 void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows, int d, int vocab, float *h,
                   hipStream_t s) {
     if (rows <= 0) return;
-    if (dtype == PC_DTYPE_F32)
+    if (dtype == KD_F32)   // the table is the caller's: fp32, or bf16 for both 16-bit kernel dtypes
         embed_kernel<float><<<rows, 256, 0, s>>>((const float *)table, tokens, d, vocab, h);
     else
         embed_kernel<bf16_t><<<rows, 256, 0, s>>>((const bf16_t *)table, tokens, d, vocab, h);
@@ -43,9 +43,11 @@ static constexpr int RMS_MAXV = 6;
 template <typename T> __device__ inline void store4(T *p, float4 v);
 template <> __device__ inline void store4<float>(float *p, float4 v) { *(float4 *)p = v; }
 template <> __device__ inline void store4<bf16_t>(bf16_t *p, float4 v) {
-    uint2 u;
-    u.x = (uint32_t)f32_to_bf16(v.x).x | ((uint32_t)f32_to_bf16(v.y).x << 16);
-    u.y = (uint32_t)f32_to_bf16(v.z).x | ((uint32_t)f32_to_bf16(v.w).x << 16);
+    uint2 u = {pack2<bf16_t>(v.x, v.y), pack2<bf16_t>(v.z, v.w)};
+    *(uint2 *)p = u;
+}
+template <> __device__ inline void store4<f16_t>(f16_t *p, float4 v) {
+    uint2 u = {pack2<f16_t>(v.x, v.y), pack2<f16_t>(v.z, v.w)};
     *(uint2 *)p = u;
 }
 
@@ -120,13 +122,15 @@ void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *ga
                     void *out, const float *slices, int S, hipStream_t s) {
     if (rows <= 0) return;
     const bool vec = (d % 4 == 0) && d <= 4 * 256 * RMS_MAXV;
-    if (dtype == PC_DTYPE_F32) {
-        if (vec) rmsnorm_kernel<float, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (float *)out, slices, S);
-        else rmsnorm_kernel<float, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (float *)out, slices, S);
-    } else {
-        if (vec) rmsnorm_kernel<bf16_t, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (bf16_t *)out, slices, S);
-        else rmsnorm_kernel<bf16_t, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (bf16_t *)out, slices, S);
-    }
+#define PC_RMS(T)                                                                                              \
+    do {                                                                                                       \
+        if (vec) rmsnorm_kernel<T, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S);  \
+        else rmsnorm_kernel<T, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S);     \
+    } while (0)
+    if (dtype == KD_F32) PC_RMS(float);
+    else if (dtype == KD_BF16) PC_RMS(bf16_t);
+    else PC_RMS(f16_t);
+#undef PC_RMS
 }
 
 // ------------------------------------------------------------------ RoPE + KV append
@@ -187,12 +191,15 @@ void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_s
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
                         KvGeom kv, int layer, void *q_out, hipStream_t s) {
     if (rows <= 0) return;
-    if (dtype == PC_DTYPE_F32)
+    if (dtype == KD_F32)
         rope_append_kernel<float><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                        layer, (float *)q_out);
-    else
+    else if (dtype == KD_BF16)
         rope_append_kernel<bf16_t><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                         layer, (bf16_t *)q_out);
+    else
+        rope_append_kernel<f16_t><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+                                                       layer, (f16_t *)q_out);
 }
 
 // ------------------------------------------------------------------ bookkeeping
@@ -227,43 +234,50 @@ __global__ void copy_block_kernel(KvGeom kv, const int32_t *__restrict__ pairs) 
 void launch_copy_block(int dtype, KvGeom kv, int n_layers, const int32_t *pairs, int n_pairs, hipStream_t s) {
     if (n_pairs <= 0) return;
     dim3 grid(n_pairs, n_layers);
-    if (dtype == PC_DTYPE_F32)
+    if (dtype == KD_F32)
         copy_block_kernel<float><<<grid, 256, 0, s>>>(kv, pairs);
-    else
+    else   // both 16-bit kernel dtypes: raw 16-bit payload
         copy_block_kernel<bf16_t><<<grid, 256, 0, s>>>(kv, pairs);
 }
 
 // ------------------------------------------------------------------ weight repacking
-template <typename T>
-__global__ void pack_rows_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t cols, int64_t dst_row0) {
+// TS: the caller's element type, TD: the kernel dtype of the copy (bf16 -> half is a value conversion)
+template <typename TS, typename TD> __device__ inline TD conv(TS v) { return from_f32<TD>(to_f32(v)); }
+
+template <typename TS, typename TD>
+__global__ void pack_rows_kernel(const TS *__restrict__ src, TD *__restrict__ dst, int64_t cols, int64_t dst_row0) {
     int64_t r = blockIdx.x;
-    for (int64_t i = threadIdx.x; i < cols; i += blockDim.x) dst[(dst_row0 + r) * cols + i] = src[r * cols + i];
+    for (int64_t i = threadIdx.x; i < cols; i += blockDim.x) dst[(dst_row0 + r) * cols + i] = conv<TS, TD>(src[r * cols + i]);
 }
-void launch_pack_rows(int dtype, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
+void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
                       hipStream_t s) {
     if (rows <= 0) return;
-    if (dtype == PC_DTYPE_F32)
-        pack_rows_kernel<float><<<(unsigned)rows, 256, 0, s>>>((const float *)src, (float *)dst, cols, dst_row0);
+    if (kd == KD_F32)
+        pack_rows_kernel<float, float><<<(unsigned)rows, 256, 0, s>>>((const float *)src, (float *)dst, cols, dst_row0);
+    else if (kd == KD_BF16)
+        pack_rows_kernel<bf16_t, bf16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, cols, dst_row0);
     else
-        pack_rows_kernel<bf16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, cols, dst_row0);
+        pack_rows_kernel<bf16_t, f16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (f16_t *)dst, cols, dst_row0);
 }
 
 // dst row 64t + c      = gate row 32t + c   (c < 32)
 // dst row 64t + 32 + c = up   row 32t + c
-template <typename T>
-__global__ void pack_gate_up_kernel(const T *__restrict__ gate, const T *__restrict__ up, T *__restrict__ dst, int d) {
+template <typename TS, typename TD>
+__global__ void pack_gate_up_kernel(const TS *__restrict__ gate, const TS *__restrict__ up, TD *__restrict__ dst, int d) {
     int64_t j = blockIdx.x;   // ffn row
     int64_t t = j / 32, c = j % 32;
     for (int i = threadIdx.x; i < d; i += blockDim.x) {
-        dst[(64 * t + c) * d + i] = gate[j * d + i];
-        dst[(64 * t + 32 + c) * d + i] = up[j * d + i];
+        dst[(64 * t + c) * d + i] = conv<TS, TD>(gate[j * d + i]);
+        dst[(64 * t + 32 + c) * d + i] = conv<TS, TD>(up[j * d + i]);
     }
 }
-void launch_pack_gate_up(int dtype, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s) {
-    if (dtype == PC_DTYPE_F32)
-        pack_gate_up_kernel<float><<<d_ff, 256, 0, s>>>((const float *)gate, (const float *)up, (float *)dst, d);
+void launch_pack_gate_up(int kd, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s) {
+    if (kd == KD_F32)
+        pack_gate_up_kernel<float, float><<<d_ff, 256, 0, s>>>((const float *)gate, (const float *)up, (float *)dst, d);
+    else if (kd == KD_BF16)
+        pack_gate_up_kernel<bf16_t, bf16_t><<<d_ff, 256, 0, s>>>((const bf16_t *)gate, (const bf16_t *)up, (bf16_t *)dst, d);
     else
-        pack_gate_up_kernel<bf16_t><<<d_ff, 256, 0, s>>>((const bf16_t *)gate, (const bf16_t *)up, (bf16_t *)dst, d);
+        pack_gate_up_kernel<bf16_t, f16_t><<<d_ff, 256, 0, s>>>((const bf16_t *)gate, (const bf16_t *)up, (f16_t *)dst, d);
 }
 
 }  // namespace pc

@@ -119,8 +119,8 @@ template <int N> __device__ inline void wait_vmcnt_le() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE, int EPI>
-__global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int EPI>
+__global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                         void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
                                                         int S, int plain) {
     constexpr int BK = 64;
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
     static_assert(EPI != EPI_SWIGLU || (BN / WN) == 64, "SwiGLU needs one 64-wide gate/up chunk per wave");
     static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
-    bf16_t *smem = (bf16_t *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
+    T *smem = (T *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
 
     // ---- which tile
     const int id = blockIdx.x;
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
 
     // ---- global -> LDS: in pass i this wave fills rows (4i + wave)*8 .. +7; lane -> (row, slot)
     const int lr = lane / 8, slot = lane % 8;
-    const bf16_t *pa[A_ITERS], *pw[W_ITERS];
+    const T *pa[A_ITERS], *pw[W_ITERS];
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i) {
         const int row = (NW * i + wave) * 8 + lr;
@@ -176,8 +176,8 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
     }
     auto issue_tile = [&](int kt, int stage) {
         const int koff = min(kt, kt1 - 1) * BK;            // past the end: a redundant reload, keeps the count constant
-        bf16_t *sa = smem + stage * STAGE_ELEMS;
-        bf16_t *sw = sa + BM * BK;
+        T *sa = smem + stage * STAGE_ELEMS;
+        T *sw = sa + BM * BK;
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + koff),
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
                                              (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * 8 * BK), 16, 0, 0);
     };
 
-    f32x16 acc[TM][TN];
+    f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -209,16 +209,17 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
         wrow[jj] = wn * (BN / WN) + jj * 32 + fr;
         wswz[jj] = (wrow[jj] >> 1) & 7;
     }
-    auto load_frags = [&](const bf16_t *sa, const bf16_t *sw, int kk, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+    typedef typename Mma<T>::frag frag_t;
+    auto load_frags = [&](const T *sa, const T *sw, int kk, frag_t (&fa)[TM], frag_t (&fb)[TN]) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8 *)(sa + arow[i] * BK + (((2 * kk + fg) ^ aswz[i]) * 8));
+        for (int i = 0; i < TM; ++i) fa[i] = *(const frag_t *)(sa + arow[i] * BK + (((2 * kk + fg) ^ aswz[i]) * 8));
 #pragma unroll
-        for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const bf16x8 *)(sw + wrow[jj] * BK + (((2 * kk + fg) ^ wswz[jj]) * 8));
+        for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const frag_t *)(sw + wrow[jj] * BK + (((2 * kk + fg) ^ wswz[jj]) * 8));
     };
     auto compute = [&](int stage) {
-        const bf16_t *sa = smem + stage * STAGE_ELEMS;
-        const bf16_t *sw = sa + BM * BK;
-        bf16x8 fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
+        const T *sa = smem + stage * STAGE_ELEMS;
+        const T *sw = sa + BM * BK;
+        frag_t fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
         load_frags(sa, sw, 0, fa[0], fb[0]);
 #pragma unroll
         for (int kk = 0; kk < BK / 16; ++kk) {
@@ -227,7 +228,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int jj = 0; jj < TN; ++jj)
-                    acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj], 0, 0, 0);
+                    acc[i][jj] = Mma<T>::m32(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj]);
         }
     };
 
@@ -257,14 +258,14 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
     for (int i = 0; i < TM; ++i) {
         const int rbase = m0 + wm * (BM / WM) + i * 32 + row_l;
         if (EPI == EPI_SWIGLU) {
-            bf16_t *C = (bf16_t *)Cv;
+            T *C = (T *)Cv;
             const int ncol = n0 + wn * 64;                 // start of this wave's gate/up chunk
             const int ocol = (ncol / 64) * 32 + col_l;
             if (ncol + 32 + col_l < N) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     int row = rbase + 8 * (v / 4) + (v % 4);
-                    if (row < M) C[(int64_t)row * (N / 2) + ocol] = f32_to_bf16(silu_f(acc[i][0][v]) * acc[i][1][v]);
+                    if (row < M) C[(int64_t)row * (N / 2) + ocol] = from_f32<T>(silu_f(acc[i][0][v]) * acc[i][1][v]);
                 }
             }
         } else {
@@ -278,18 +279,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const bf16_t *_
                     if (row >= M) continue;
                     if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
                     if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
-                    if (EPI == EPI_STORE_T) ((bf16_t *)Cv)[(int64_t)row * N + col] = f32_to_bf16(acc[i][jj][v]);
+                    if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(acc[i][jj][v]);
                 }
             }
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
-    static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(bf16_t);
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
+    static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(T);
     static constexpr bool swiglu_ok = (BN / WN == 64);
     template <int E> static void set_attr() {
-        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, E>,
+        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, E>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static void init() {
@@ -304,15 +305,15 @@ template <int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
         const int units = nb * split;
         const int plain = (split == 1 && mb > 4) ? 1 : 0;
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
-        const bf16_t *a = (const bf16_t *)A, *w = (const bf16_t *)W;
+        const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
             case EPI_SWIGLU:
                 if constexpr (swiglu_ok)
-                    gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
                 break;
-            default: gemm_mfma_kernel<BM, BN, WM, WN, NSTAGE, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
         }
     }
     // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
@@ -329,27 +330,42 @@ template <int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
     }
 };
 
-typedef MfmaCfg<128, 128, 2, 2, 4> CfgLarge;   // wave tile 64x64, 128 KB of LDS: one block per CU, 3 tiles in flight
-typedef MfmaCfg<64, 64, 2, 2, 4> CfgSmall;     // wave tile 32x32: many blocks for the small projections
-typedef MfmaCfg<256, 128, 4, 2, 3> CfgTall;     // 8 waves, wave tile 64x64, 144 KB of LDS: every decode row in one block
-
-void gemm_init() {
-    CfgLarge::init();
-    CfgSmall::init();
-    CfgTall::init();
+template <typename T> static void gemm_init_t() {
+    MfmaCfg<T, 128, 128, 2, 2, 4>::init();
+    MfmaCfg<T, 64, 64, 2, 2, 4>::init();
+    MfmaCfg<T, 256, 128, 4, 2, 3>::init();
 }
+void gemm_init() {
+    gemm_init_t<bf16_t>();
+    gemm_init_t<f16_t>();
+}
+
+template <typename T>
+static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
+                              size_t slice_cap_floats, hipStream_t s);
 
 int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
                 float *slices, size_t slice_cap_floats, hipStream_t s) {
     if (M <= 0 || N <= 0) return 1;
-    if (dtype == PC_DTYPE_F32) {
+    if (dtype == KD_F32) {
         gemm_simt<float>(A, W, C, M, N, K, epi, s);
         return 1;
     }
     if (impl == 0 || (K % 64) != 0) {
-        gemm_simt<bf16_t>(A, W, C, M, N, K, epi, s);
+        if (dtype == KD_BF16) gemm_simt<bf16_t>(A, W, C, M, N, K, epi, s);
+        else gemm_simt<f16_t>(A, W, C, M, N, K, epi, s);
         return 1;
     }
+    if (dtype == KD_BF16) return gemm_mfma_dispatch<bf16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, s);
+    return gemm_mfma_dispatch<f16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, s);
+}
+
+template <typename T>
+static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
+                              size_t slice_cap_floats, hipStream_t s) {
+    typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;   // wave tile 64x64, 128 KB of LDS: one block per CU, 3 tiles in flight
+    typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;     // wave tile 32x32: many blocks for the small projections
+    typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;    // 8 waves, wave tile 64x64, 144 KB of LDS: every decode row in one block
     if (M > 512) {   // prefill: plenty of tiles
         CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
         return 1;

@@ -29,11 +29,63 @@ __host__ __device__ inline bf16_t f32_to_bf16(float f) {
     return r;
 }
 
+// ---------------------------------------------------------------- f16 (IEEE half)
+struct f16_t {
+    uint16_t x;
+};
+__device__ inline float f16_to_f32(f16_t v) { return (float)__builtin_bit_cast(_Float16, v.x); }
+// round to nearest even, saturating at the largest finite half instead of overflowing to infinity
+__device__ inline f16_t f32_to_f16(float f) {
+    f = fminf(fmaxf(f, -65504.f), 65504.f);
+    f16_t r;
+    r.x = __builtin_bit_cast(uint16_t, (_Float16)f);
+    return r;
+}
+
 __device__ inline float to_f32(float v) { return v; }
 __device__ inline float to_f32(bf16_t v) { return bf16_to_f32(v); }
+__device__ inline float to_f32(f16_t v) { return f16_to_f32(v); }
 template <typename T> __device__ inline T from_f32(float f);
 template <> __device__ inline float from_f32<float>(float f) { return f; }
 template <> __device__ inline bf16_t from_f32<bf16_t>(float f) { return f32_to_bf16(f); }
+template <> __device__ inline f16_t from_f32<f16_t>(float f) { return f32_to_f16(f); }
+// two values packed into one 32-bit word (low half first)
+template <typename T> __device__ inline uint32_t pack2(float a, float b) {
+    return (uint32_t)from_f32<T>(a).x | ((uint32_t)from_f32<T>(b).x << 16);
+}
+
+// Kernel data types: the type of activations, KV cache and the library's weight copies.
+//   KD_F32   fp32 models
+//   KD_BF16  bf16 models, bf16 activations
+//   KD_F16   bf16 models, IEEE-half activations and weight copies (bf16 weights convert to half without
+//            loss above 6.1e-5 in magnitude, with an absolute error below 3e-8 under it); three more
+//            significand bits than bf16 at the same matrix-core rate
+enum KernelDtype { KD_F32 = 0, KD_BF16 = 1, KD_F16 = 2 };
+
+// matrix-core products on 8-element fragments
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    typedef bf16x8_t frag;
+    __device__ static inline f32x16_t m32(frag a, frag b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    __device__ static inline f32x4_t m16(frag a, frag b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+    }
+};
+template <> struct Mma<f16_t> {
+    typedef f16x8_t frag;
+    __device__ static inline f32x16_t m32(frag a, frag b, f32x16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    __device__ static inline f32x4_t m16(frag a, frag b, f32x4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 // ---------------------------------------------------------------- errors
 void set_error(const char *fmt, ...);
@@ -79,7 +131,7 @@ enum Epilogue {
 };
 
 // ---------------------------------------------------------------- kernel launchers
-// (each validates nothing: callers pass shapes that the context has checked)
+// (each validates nothing: callers pass shapes that the context has checked; `dtype` is a KernelDtype)
 void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows, int d, int vocab, float *h,
                   hipStream_t s);
 // out[r] = norm(h[src_row ? src_row[r] : r]) * gain, in the model dtype.  With S > 1 slices
@@ -106,15 +158,15 @@ void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, co
                            const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
                            hipStream_t s);
 // Matrix-core attention (bf16).  Prefill: rows of each prompt are contiguous and start at position 0.
-void launch_attention_prefill_mfma(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
-                                   int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s);
+void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
+                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s);
 // Decode: one query row per sequence.  n_splits = attention_decode_splits(...): with one split the
 // kernel writes `out` itself, otherwise it leaves partial results in `scratch` for the merge pass.
 int attention_decode_splits(int rows, int n_kv_heads, int max_ctx);
-void launch_attention_decode_mfma(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                  KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s);
-void launch_attention_decode_merge(const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, int n_splits,
-                                   float *scratch, void *out, hipStream_t s);
+void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
+                                  int hq, KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s);
+void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
+                                   int n_splits, float *scratch, void *out, hipStream_t s);
 size_t attention_decode_scratch_floats(int max_rows, int hq, int hd);
 
 void launch_advance_len(int32_t *slot_len, const int32_t *row_slot, int rows, hipStream_t s);
@@ -131,9 +183,9 @@ void launch_select_commit(const float *p_hat, int P, float lo, float hi, float s
 void launch_advantages(const float *rewards, const int32_t *off, int P, float eps, float *adv, float *mu, float *sigma,
                        hipStream_t s);
 
-// weight repacking at context creation
-void launch_pack_rows(int dtype, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
+// weight repacking at context creation; the source has the model's dtype, the copy the kernel dtype `kd`
+void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
                       hipStream_t s);   // dst[dst_row0 + r] = src[r]
-void launch_pack_gate_up(int dtype, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s);
+void launch_pack_gate_up(int kd, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s);
 
 }  // namespace pc

@@ -160,21 +160,24 @@ def test_bf16_plain_alu_path():
     _check(BF, w, prompts, out, 5, 2e-2, range(6))
 
 
-@pytest.mark.parametrize("model,lens,G,T,bs,std", [
-    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.02),  # the workloads' init: absolute 2e-2 bound
-    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.05),  # 6 query heads per kv head, ragged, partial blocks
-    (BF4, [600, 17, 520], 3, 40, 32, 0.05),       # long contexts cut into splits, 4 heads per kv head
-    (BF, [40] * 64 + [7], 4, 6, 64, 0.02),        # 260 sequences: one split per sequence, direct output
-    (BF8, [100, 31], 3, 10, 64, 0.02),            # split-K in the large-tile GEMM
+@pytest.mark.parametrize("model,lens,G,T,bs,std,act", [
+    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.02, "f16"),   # the workloads' init: absolute 2e-2 bound
+    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.02, "bf16"),  # same with bfloat16 activations
+    (BF, [70, 33, 128, 5, 64], 4, 24, 64, 0.05, "f16"),   # 6 query heads per kv head, ragged, partial blocks
+    (BF4, [600, 17, 520], 3, 40, 32, 0.05, "f16"),        # long contexts cut into splits, 4 heads per kv head
+    (BF4, [600, 17, 520], 3, 40, 32, 0.05, "bf16"),
+    (BF, [40] * 64 + [7], 4, 6, 64, 0.02, "f16"),         # 260 sequences: one split per sequence, direct output
+    (BF8, [100, 31], 3, 10, 64, 0.02, "f16"),             # split-K in the large-tile GEMM
+    (BF8, [100, 31], 3, 10, 64, 0.02, "bf16"),
 ])
-def test_bf16_matrix_core_path(model, lens, G, T, bs, std):
-    say("bf16 matrix-core path lens=%s G=%d T=%d std=%g" % (lens, G, T, std))
+def test_bf16_matrix_core_path(model, lens, G, T, bs, std, act):
+    say("bf16 model, matrix-core path, %s activations, lens=%s G=%d T=%d std=%g" % (act, lens[:6], G, T, std))
     w = workloads.perturb_norm_gains(workloads.make_weights(model, 3, std=std), 10)
     toks, cu = workloads.make_ragged_prompts(lens, model.vocab, 8)
     prompts = [toks[cu[i]:cu[i + 1]] for i in range(len(lens))]
     out = _run_generate(model, w, prompts, G, T, 21, dict(block_size=bs, kv_pool_bytes=512 << 20,
                                                          max_slots=len(lens) * (G + 1) + 8, max_ctx=1024,
-                                                         max_batch_rows=1024))
+                                                         max_batch_rows=1024, act_dtype=act))
     for q in range(len(lens)):
         want = decoder.forward_full(model, w, prompts[q], rows=[lens[q] - 1])[0]
         assert np.abs(want - out["last"][q]).max() <= 2e-2 * max(1.0, np.abs(want).max())
