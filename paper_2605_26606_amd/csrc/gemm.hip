@@ -111,25 +111,28 @@ static constexpr int N_XCD = 8;   // MI355X: 8 accelerator dies, each with its o
 // Data path: global memory -> LDS directly (global_load_lds_dwordx4, no register staging), NSTAGE
 // tiles deep, one barrier per K tile.  A wave-wide load lands as 1 KB of consecutive LDS (8 rows of
 // 64 k); to keep the 128-bit fragment reads conflict free without padding, the 16-byte chunk c of
-// row r is stored at chunk slot c ^ ((r >> 1) & 7) (the lane fetches the chunk its slot must hold).
-// K must be a multiple of 64 here.
+// row r is stored at chunk slot c ^ swz(r) (the lane fetches the chunk its slot must hold), where swz
+// makes any 16 consecutive rows hit 16 different 16-byte bank groups.  K must be a multiple of 64 here.
 __device__ inline void wait_vmcnt(int) {}
 template <int N> __device__ inline void wait_vmcnt_le() {
     // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = bits 15:14 | 3:0)
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int EPI>
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK, int EPI>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                         void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
                                                         int S, int plain) {
-    constexpr int BK = 64;
+    constexpr int CPR = BK / 8;                           // 16-byte chunks per tile row
+    constexpr int RPL = 64 / CPR;                         // tile rows one wave-wide load covers
+    constexpr int SWZ_DIV = 16 / CPR;                     // rows that share a swizzle value
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int NW = WM * WN;                           // waves per block
-    constexpr int A_ITERS = BM / (8 * NW), W_ITERS = BN / (8 * NW);   // the waves move 8*NW rows of 64 k per pass
+    constexpr int A_ITERS = BM / (RPL * NW), W_ITERS = BN / (RPL * NW);   // the waves move RPL*NW rows of BK k per pass
     constexpr int LOADS = A_ITERS + W_ITERS;              // load instructions per thread per K tile
     constexpr int STAGE_ELEMS = (BM + BN) * BK;
-    static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "whole passes");
+    static_assert(BK == 64 || BK == 32, "K tile");
+    static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "whole passes");
     static_assert(EPI != EPI_SWIGLU || (BN / WN) == 64, "SwiGLU needs one 64-wide gate/up chunk per wave");
     static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -160,18 +163,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     const int kt0 = z * per, kt1 = min(KT, kt0 + per);
 
     // ---- global -> LDS: in pass i this wave fills rows (4i + wave)*8 .. +7; lane -> (row, slot)
-    const int lr = lane / 8, slot = lane % 8;
+    const int lr = lane / CPR, slot = lane % CPR;
     const T *pa[A_ITERS], *pw[W_ITERS];
 #pragma unroll
     for (int i = 0; i < A_ITERS; ++i) {
-        const int row = (NW * i + wave) * 8 + lr;
-        const int chunk = slot ^ ((row >> 1) & 7);
+        const int row = (NW * i + wave) * RPL + lr;
+        const int chunk = slot ^ ((row / SWZ_DIV) & (CPR - 1));
         pa[i] = A + (int64_t)min(m0 + row, M - 1) * K + chunk * 8;   // rows past the end: clamped, results discarded
     }
 #pragma unroll
     for (int i = 0; i < W_ITERS; ++i) {
-        const int row = (NW * i + wave) * 8 + lr;
-        const int chunk = slot ^ ((row >> 1) & 7);
+        const int row = (NW * i + wave) * RPL + lr;
+        const int chunk = slot ^ ((row / SWZ_DIV) & (CPR - 1));
         pw[i] = W + (int64_t)min(n0 + row, N - 1) * K + chunk * 8;
     }
     auto issue_tile = [&](int kt, int stage) {
@@ -181,11 +184,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + koff),
-                                             (__attribute__((address_space(3))) void *)(sa + (NW * i + wave) * 8 * BK), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void *)(sa + (NW * i + wave) * RPL * BK), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < W_ITERS; ++i)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pw[i] + koff),
-                                             (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * 8 * BK), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
     };
 
     f32x16_t acc[TM][TN];
@@ -202,12 +205,12 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         arow[i] = wm * (BM / WM) + i * 32 + fr;
-        aswz[i] = (arow[i] >> 1) & 7;
+        aswz[i] = (arow[i] / SWZ_DIV) & (CPR - 1);
     }
 #pragma unroll
     for (int jj = 0; jj < TN; ++jj) {
         wrow[jj] = wn * (BN / WN) + jj * 32 + fr;
-        wswz[jj] = (wrow[jj] >> 1) & 7;
+        wswz[jj] = (wrow[jj] / SWZ_DIV) & (CPR - 1);
     }
     typedef typename Mma<T>::frag frag_t;
     auto load_frags = [&](const T *sa, const T *sw, int kk, frag_t (&fa)[TM], frag_t (&fb)[TN]) {
@@ -286,11 +289,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     }
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg {
-    static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * 64 * sizeof(T);
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> struct MfmaCfg {
+    static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * BK * sizeof(T);
     static constexpr bool swiglu_ok = (BN / WN == 64);
     template <int E> static void set_attr() {
-        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, E>,
+        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, E>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static void init() {
@@ -307,19 +310,19 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
             case EPI_SWIGLU:
                 if constexpr (swiglu_ok)
-                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
                 break;
-            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
         }
     }
     // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
     static int pick_split(int M, int N, int K, size_t slice_cap_floats, int want_blocks) {
         const int64_t tiles = (int64_t)((N + BN - 1) / BN) * ((M + BM - 1) / BM);
-        const int KT = (K + 63) / 64;
+        const int KT = K / BK;
         int64_t split = (want_blocks + tiles / 2) / tiles;
         split = std::min<int64_t>(split, KT / 4);
         split = std::min<int64_t>(split, 8);
@@ -331,9 +334,11 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE> struct MfmaCfg
 };
 
 template <typename T> static void gemm_init_t() {
-    MfmaCfg<T, 128, 128, 2, 2, 4>::init();
-    MfmaCfg<T, 64, 64, 2, 2, 4>::init();
+    MfmaCfg<T, 256, 128, 4, 2, 3, 32>::init();
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
+    MfmaCfg<T, 128, 128, 2, 2, 4>::init();
+    MfmaCfg<T, 128, 64, 2, 2, 4>::init();
+    MfmaCfg<T, 64, 64, 2, 2, 4>::init();
 }
 void gemm_init() {
     gemm_init_t<bf16_t>();
@@ -363,36 +368,34 @@ int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int 
 template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
                               size_t slice_cap_floats, hipStream_t s) {
-    typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;   // wave tile 64x64, 128 KB of LDS: one block per CU, 3 tiles in flight
-    typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;     // wave tile 32x32: many blocks for the small projections
-    typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;    // 8 waves, wave tile 64x64, 144 KB of LDS: every decode row in one block
+    // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
+    typedef MfmaCfg<T, 256, 128, 4, 2, 3, 32> CfgPrefill;   // 8 waves, 72 KB of LDS: two blocks per CU
+    typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
+    typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
+    typedef MfmaCfg<T, 128, 64, 2, 2, 4> CfgMid;            // wave tile 64x32: long-K projections cut into K slices
+    typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;           // wave tile 32x32: many blocks for the small projections
     if (M > 512) {   // prefill: plenty of tiles
-        CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
+        CfgPrefill::run(A, W, C, M, N, K, epi, 1, s);
         return 1;
     }
     // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
-    const int64_t large_tiles = (int64_t)((N + 127) / 128) * ((M + 127) / 128);
-    const bool big = epi == EPI_SWIGLU || large_tiles >= 192 || (int64_t)N * K >= (int64_t)8 << 20;
-    if (big && M > 128 && (N + 127) / 128 >= 96) {   // all rows in one 256-row block: a weight tile is fetched once
-        const int split = can_split ? CfgTall::pick_split(M, N, K, slice_cap_floats, 192) : 1;
-        if (split > 1) {
-            CfgTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
-            return split;
-        }
-        CfgTall::run(A, W, C, M, N, K, epi, 1, s);
+    const int nb128 = (N + 127) / 128;
+    if (epi == EPI_SWIGLU || nb128 >= 96) {   // wide outputs: no K slices needed
+        if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, s);   // a weight tile is fetched by exactly one block
+        else CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
         return 1;
     }
-    if (big) {
-        const int split = can_split ? CfgLarge::pick_split(M, N, K, slice_cap_floats, 192) : 1;
+    if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the feed-forward down projection)
+        const int split = can_split ? CfgMid::pick_split(M, N, K, slice_cap_floats, 240) : 1;
         if (split > 1) {
-            CfgLarge::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+            CfgMid::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
             return split;
         }
-        CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
+        CfgMid::run(A, W, C, M, N, K, epi, 1, s);
         return 1;
     }
-    const int split = can_split ? CfgSmall::pick_split(M, N, K, slice_cap_floats, 128) : 1;
+    const int split = can_split ? CfgSmall::pick_split(M, N, K, slice_cap_floats, 192) : 1;
     if (split > 1) {
         CfgSmall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
         return split;
