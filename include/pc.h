@@ -121,8 +121,11 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *weights,
 pc_status pc_destroy(pc_ctx *ctx);
 pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value);
 /* Sums the event pairs recorded since the last reset: total_ms (host double) and launches (host
- * int64) over all timed launches.  SYNCHRONISES on the recorded events.  reset != 0 recycles them. */
-pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, int32_t reset);
+ * int64) over all timed launches; empty_ms / empty_pairs (host, may be NULL): the same for the
+ * calibration pairs (one per timed step, recorded back to back with nothing between, i.e. what the
+ * bracket itself costs).  SYNCHRONISES on the recorded events.  reset != 0 recycles them. */
+pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, double *empty_ms,
+                         int64_t *empty_pairs, int32_t reset);
 /* Number of free KV blocks / total KV blocks (host bookkeeping, no GPU work). */
 pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks);
 

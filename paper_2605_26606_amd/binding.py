@@ -66,7 +66,7 @@ def library() -> C.CDLL:
             "pc_destroy": [vp],
             "pc_set_option": [vp, i32, i32],
             "pc_kv_blocks": [vp, C.POINTER(i64), C.POINTER(i64)],
-            "pc_timing_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), i32],
+            "pc_timing_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(i64), i32],
             "pc_prefill_shared": [vp, vp, vp, i32, vp, vp, vp],
             "pc_fork": [vp, vp, i32, i32, vp, vp],
             "pc_decode_step": [vp, vp, vp, i32, vp, vp],
@@ -170,10 +170,12 @@ def pc_set_option(ctx: Context, option: int, value: int):
 
 
 def pc_timing_read(ctx: Context, reset: bool = True):
-    """(total_ms, launches) over the event pairs recorded since the last reset; synchronises."""
-    ms, n = C.c_double(), C.c_int64()
-    _check(library().pc_timing_read(ctx.handle, C.byref(ms), C.byref(n), 1 if reset else 0))
-    return ms.value, n.value
+    """(total_ms, launches, empty_ms, empty_pairs) over the event pairs recorded since the last
+    reset (the "empty" pairs bracket nothing: the cost of the bracket); synchronises."""
+    ms, n, ems, en = C.c_double(), C.c_int64(), C.c_double(), C.c_int64()
+    _check(library().pc_timing_read(ctx.handle, C.byref(ms), C.byref(n), C.byref(ems), C.byref(en),
+                                    1 if reset else 0))
+    return ms.value, n.value, ems.value, en.value
 
 
 def pc_kv_blocks(ctx: Context):

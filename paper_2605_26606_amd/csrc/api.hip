@@ -26,6 +26,7 @@ struct Slot {
     bool is_prompt = false;
     int len = 0;          // tokens whose K/V are in the cache
     int capacity = 0;     // tokens the slot's blocks can hold
+    int prompt = -1;      // sequences: the prompt slot they were forked from
     std::vector<int32_t> blocks;
 };
 
@@ -62,6 +63,7 @@ struct pc_ctx {
     float *slices = nullptr;       // split-K slices of the decode projections
     size_t slice_cap = 0;
     std::vector<int32_t> dec_seq;     // sequence list currently resident in d_dec_slot
+    int dec_group = 1;                // consecutive entries of dec_seq that share a prompt
     std::vector<int32_t> stamp;
     int32_t stamp_gen = 0;
     // options
@@ -79,6 +81,8 @@ struct pc_ctx {
     int time_class = -1;
     std::vector<hipEvent_t> ev_pool;
     size_t ev_used = 0;
+    std::vector<hipEvent_t> ev_empty;   // back-to-back pairs with nothing between: the cost of the bracket itself
+    size_t ev_empty_used = 0;
 
     KvGeom geom() const {
         KvGeom g;
@@ -107,6 +111,7 @@ template <typename T> pc_status dev_alloc(T **p, size_t n_elems) {
 void free_all(pc_ctx *ctx) {
     if (ctx->exec) (void)hipGraphExecDestroy(ctx->exec);
     for (hipEvent_t e : ctx->ev_pool) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ctx->ev_empty) (void)hipEventDestroy(e);
     auto fr = [](const void *p) { if (p) (void)hipFree(const_cast<void *>(p)); };
     for (auto p : ctx->wqkv) fr(p);
     for (auto p : ctx->wo) fr(p);
@@ -201,7 +206,7 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
                 {
                     Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
                     launch_attention_decode_mfma(dt, ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
-                                                 ctx->attn_scratch, ctx->attn, st);
+                                                 ctx->dec_group, ctx->attn_scratch, ctx->attn, st);
                 }
                 launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, n_splits,
                                               ctx->attn_scratch, ctx->attn, st);
@@ -437,10 +442,11 @@ pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value) {
     return PC_OK;
 }
 
-pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, int32_t reset) {
+pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, double *empty_ms, int64_t *empty_pairs,
+                         int32_t reset) {
     if (!ctx || !total_ms || !launches) PC_FAIL(PC_ERR_INVALID_ARG, "pc_timing_read: null argument");
-    double tot = 0.0;
-    int64_t cnt = 0;
+    double tot = 0.0, etot = 0.0;
+    int64_t cnt = 0, ecnt = 0;
     for (size_t i = 0; i + 1 < ctx->ev_used; i += 2) {
         PC_HIP(hipEventSynchronize(ctx->ev_pool[i + 1]));
         float ms = 0.f;
@@ -448,9 +454,18 @@ pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, int32
         tot += (double)ms;
         ++cnt;
     }
+    for (size_t i = 0; i + 1 < ctx->ev_empty_used; i += 2) {
+        PC_HIP(hipEventSynchronize(ctx->ev_empty[i + 1]));
+        float ms = 0.f;
+        PC_HIP(hipEventElapsedTime(&ms, ctx->ev_empty[i], ctx->ev_empty[i + 1]));
+        etot += (double)ms;
+        ++ecnt;
+    }
     *total_ms = tot;
     *launches = cnt;
-    if (reset) ctx->ev_used = 0;
+    if (empty_ms) *empty_ms = etot;
+    if (empty_pairs) *empty_pairs = ecnt;
+    if (reset) ctx->ev_used = ctx->ev_empty_used = 0;
     return PC_OK;
 }
 
@@ -587,6 +602,7 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
         Slot &s = ctx->slots[slot];
         s.used = true;
         s.is_prompt = false;
+        s.prompt = prompt_handle[i];
         s.len = ps.len;
         const int n_full = ps.len / bs, total = (ps.len + max_new_tokens + bs - 1) / bs;
         for (int b = 0; b < n_full; ++b) {
@@ -659,6 +675,14 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
     if ((int)ctx->dec_seq.size() != n || memcmp(ctx->dec_seq.data(), seq, (size_t)n * 4) != 0) {
         ctx->dec_seq.assign(seq, seq + n);
         ctx->list_version++;
+        // rollouts of one prompt that sit next to each other in the list share their prefix blocks
+        int g = 1;
+        while (g < n && ctx->slots[seq[g]].prompt == ctx->slots[seq[0]].prompt) ++g;
+        bool uniform = (n % g == 0);
+        for (int i = 0; uniform && i < n; i += g)
+            for (int k = 1; k < g; ++k)
+                if (ctx->slots[seq[i + k]].prompt != ctx->slots[seq[i]].prompt) uniform = false;
+        ctx->dec_group = uniform ? g : 1;
         PC_HIP(hipMemcpyAsync(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
     }
     (void)max_len;
@@ -690,6 +714,16 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
         }
         PC_HIP(hipGraphLaunch(ctx->exec, st));
     } else {
+        if (ctx->time_class >= 0) {   // calibrate: an event pair around nothing
+            for (int k = 0; k < 2; ++k) {
+                if (ctx->ev_empty_used == ctx->ev_empty.size()) {
+                    hipEvent_t e;
+                    if (hipEventCreate(&e) != hipSuccess) break;
+                    ctx->ev_empty.push_back(e);
+                }
+                (void)hipEventRecord(ctx->ev_empty[ctx->ev_empty_used++], st);
+            }
+        }
         enqueue_decode(ctx, tokens_in, n, logits, st);
         ctx->time_class = -1;   // timing covers one step
         pc_status rc = check_launch();

@@ -292,18 +292,27 @@ __device__ inline int split_len(int ctx, int n_splits) {
     return ((ctx + n_splits - 1) / n_splits + ROUND - 1) / ROUND * ROUND;
 }
 
-// grid (splits, kv heads, rows), 4 waves per block; wave w takes the tiles w, w+4, ... of the split.
+// One block per (row, kv head, context split), 4 waves; wave w takes the tiles w, w+4, ... of the split.
 // DIRECT (one split): the block normalises and writes the attention output itself.
+// Block order: `group` consecutive rows are the rollouts of one prompt and read the same prefix blocks;
+// the 1-D grid is laid out so that those blocks run back to back on ONE die (workgroup i runs on die
+// i % 8), which then fetches the shared prefix from HBM once and serves the other rollouts from its L2.
 template <typename T, bool DIRECT>
 __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__restrict__ q,
                                                                     const int32_t *__restrict__ row_slot,
                                                                     const int32_t *__restrict__ slot_len, int hq,
-                                                                    KvGeom kv, int layer, float *__restrict__ part_ml,
+                                                                    KvGeom kv, int layer, int rows, int n_splits,
+                                                                    int group, float *__restrict__ part_ml,
                                                                     float *__restrict__ part_o,
                                                                     T *__restrict__ out) {
     __shared__ float sm[DEC_WAVES][16], sl[DEC_WAVES][16];
     __shared__ float so[DEC_WAVES][16][HD];
-    const int sp = blockIdx.x, n_splits = gridDim.x, kvh = blockIdx.y, r = blockIdx.z;
+    const int b = blockIdx.x, die = b % 8, j = b / 8;
+    const int unit = (j / group) * 8 + die;              // (prompt, kv head, split)
+    const int per_prompt = kv.n_kv_heads * n_splits;
+    if (unit >= (rows / group) * per_prompt) return;
+    const int r = (unit / per_prompt) * group + j % group;
+    const int kvh = (unit / n_splits) % kv.n_kv_heads, sp = unit % n_splits;
     const int slot = row_slot[r];
     const int ctx = slot_len[slot] + 1;
     const int len = split_len(ctx, n_splits);
@@ -413,23 +422,28 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
 
 template <typename T>
 static void decode_launch(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
-                          int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
+                          int layer, int n_splits, int group, float *scratch, void *out, hipStream_t s) {
     float *part_ml = scratch;
     float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
-    dim3 grid(n_splits, kv.n_kv_heads, rows);
+    if (group < 1 || rows % group) group = 1;
+    const int units = (rows / group) * kv.n_kv_heads * n_splits;
+    const unsigned grid = (unsigned)((units + 7) / 8 * 8 * group);
     if (n_splits == 1)
-        attention_decode_mfma_kernel<T, true><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer,
-                                                                   part_ml, part_o, (T *)out);
+        attention_decode_mfma_kernel<T, true><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer, rows,
+                                                                   n_splits, group, part_ml, part_o, (T *)out);
     else
-        attention_decode_mfma_kernel<T, false><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer,
-                                                                    part_ml, part_o, (T *)out);
+        attention_decode_mfma_kernel<T, false><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer, rows,
+                                                                    n_splits, group, part_ml, part_o, (T *)out);
 }
 
 void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
-                                  int hq, KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s) {
+                                  int hq, KvGeom kv, int layer, int n_splits, int group, float *scratch, void *out,
+                                  hipStream_t s) {
     if (rows <= 0) return;
-    if (dtype == KD_BF16) decode_launch<bf16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, scratch, out, s);
-    else decode_launch<f16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, scratch, out, s);
+    if (dtype == KD_BF16)
+        decode_launch<bf16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, s);
+    else
+        decode_launch<f16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, s);
 }
 
 // only needed when n_splits > 1

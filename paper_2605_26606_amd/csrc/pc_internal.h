@@ -163,8 +163,10 @@ void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_r
 // Decode: one query row per sequence.  n_splits = attention_decode_splits(...): with one split the
 // kernel writes `out` itself, otherwise it leaves partial results in `scratch` for the merge pass.
 int attention_decode_splits(int rows, int n_kv_heads, int max_ctx);
+// `group`: consecutive rows that share a prompt (1 if unknown): they are scheduled on one die.
 void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
-                                  int hq, KvGeom kv, int layer, int n_splits, float *scratch, void *out, hipStream_t s);
+                                  int hq, KvGeom kv, int layer, int n_splits, int group, float *scratch, void *out,
+                                  hipStream_t s);
 void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
                                    int n_splits, float *scratch, void *out, hipStream_t s);
 size_t attention_decode_scratch_floats(int max_rows, int hq, int hd);

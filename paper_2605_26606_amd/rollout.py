@@ -162,7 +162,7 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     mark()
     crow = np.repeat(kept.astype(np.int32), ncom)
     gc = generate(ctx, handles[crow], crow, last_logits, _seq_uids(uids[kept], range(npil, npil + ncom)), T,
-                  wl.temperature, seed, eos_id, eos_logit_bias, stream, timed_steps=ts_c, **tkw)
+                  wl.temperature, seed, eos_id, eos_logit_bias, stream, timed_steps=ts_c)   # timing: pilot pass only
     if timed_steps is not None:
         # (pass, step, sequences, prompts whose prefix those sequences share)
         timed_steps.extend(("pilot", t, n, P) for t, n in ts_p)
