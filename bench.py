@@ -71,6 +71,11 @@ def main():
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--time-every", type=int, default=64)
+    ap.add_argument("--no-graph", action="store_true",
+                    help="launch decode steps eagerly (for counter runs: the profiler's counter mode and HIP graphs "
+                         "do not go together)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (the known-size reference of the counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported (no multi-GPU path "
@@ -96,6 +101,8 @@ def main():
     kv_tokens = P * Lp + n_max * (T + 64) + 4096
     ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
                      max_slots=P + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
+    if args.no_graph:
+        pc.pc_set_option(ctx, pc.PC_OPT_USE_GRAPH, 0)
     cu = (np.arange(P + 1) * Lp).astype(np.int32)
     toks = torch.from_numpy(prompts.reshape(-1).astype(np.int32)).to(dev)
     eos_id = workloads.make_eos_id(m.vocab, wl.seed_eos) if wl.eos else -1
@@ -170,6 +177,12 @@ def main():
         "prefill": {"ms": round(prefill_ms, 2), "TFLOPs": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9, 1),
                     "frac_mfma": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
+    if args.calibrate_copy:   # rocprofv3 --pmc runs scale FETCH_SIZE / WRITE_SIZE by what this copy reads
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, w, prompts, uids, wl.seed_sampler)
     ctx.close()

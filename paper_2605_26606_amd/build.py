@@ -10,6 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpc.so")
+KERNEL_BENCH = os.path.join(HERE, "kernel_bench")   # standalone driver of the hot kernels (tuning, counter runs)
 SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "allocation.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are kept out of the generated code on purpose
@@ -42,6 +43,8 @@ def build(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
         outs = list(ex.map(one, range(len(SOURCES))))
     outs.append(_run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]))
+    outs.append(_run([cc, *[f for f in FLAGS if f != "-fPIC"], "-Wno-unused-value", os.path.join(CSRC, "kernel_bench.hip"),
+                      "-o", KERNEL_BENCH]))
     if verbose:
         sys.stdout.write("\n".join(o for o in outs if o.strip()) + "\n")
     return LIB
