@@ -208,7 +208,7 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
                     launch_attention_decode_mfma(dt, ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
                                                  ctx->dec_group, ctx->attn_scratch, ctx->attn, st);
                 }
-                launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, n_splits,
+                launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, m.n_kv_heads, n_splits,
                                               ctx->attn_scratch, ctx->attn, st);
             }
         } else {

@@ -270,43 +270,51 @@ void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_r
 }
 
 // ---------------------------------------------------------------- decode
-static constexpr int DEC_WAVES = 4;
-static constexpr int ROUND = 32 * DEC_WAVES;   // tokens one block consumes per pass of its four waves
+// A block has 4 waves when the batch alone fills the chip twice over (two blocks per CU), 8 waves when
+// there are too few (row, kv head) pairs for that: one block per CU then, and every wave walks half as
+// many tiles, which is what counts when the launch is bound by latency rather than by bandwidth.
+static int decode_waves(int rows, int n_kv_heads) { return rows * n_kv_heads <= 256 ? 8 : 4; }
 
-// Number of context splits: enough blocks to fill the chip, none when the batch alone does.
+// Number of context splits: enough blocks to fill the chip, none when the batch alone nearly does
+// (a merge pass costs more than a partly filled chip).
 int attention_decode_splits(int rows, int n_kv_heads, int max_ctx) {
     const int blocks = rows * n_kv_heads;
-    int s = (512 + blocks - 1) / blocks;
-    s = std::min(s, std::max(1, (max_ctx + 2 * ROUND - 1) / (2 * ROUND)));
+    if (blocks >= 192) return 1;
+    const int round = 32 * decode_waves(rows, n_kv_heads);
+    int s = (384 + blocks - 1) / blocks;
+    s = std::min(s, std::max(1, (max_ctx + round - 1) / round));
     return std::max(1, std::min(s, 16));
 }
 
 // scratch per (row, q head, split): (max, sum) and the unnormalised output [HD].
-// rows * splits(rows) never exceeds rows + 512 (splits > 1 only while rows * kv heads < 512).
+// rows * splits(rows) never exceeds rows + 512 (splits > 1 only while rows * kv heads < 192, and then
+// splits <= 384 / (rows * kv heads) + 1).
 size_t attention_decode_scratch_floats(int max_rows, int hq, int hd) {
     return (size_t)(max_rows + 512) * hq * (hd + 2);
 }
 
-// Every row cuts ITS context into n_splits equal pieces (rounded up to whole passes).
-__device__ inline int split_len(int ctx, int n_splits) {
-    return ((ctx + n_splits - 1) / n_splits + ROUND - 1) / ROUND * ROUND;
+// Every row cuts ITS context into n_splits equal pieces (rounded up to whole passes of `round` tokens).
+__device__ inline int split_len(int ctx, int n_splits, int round) {
+    return ((ctx + n_splits - 1) / n_splits + round - 1) / round * round;
 }
 
-// One block per (row, kv head, context split), 4 waves; wave w takes the tiles w, w+4, ... of the split.
+// One block per (row, kv head, context split), NW waves; wave w takes the tiles w, w+NW, ... of the split.
 // DIRECT (one split): the block normalises and writes the attention output itself.
 // Block order: `group` consecutive rows are the rollouts of one prompt and read the same prefix blocks;
 // the 1-D grid is laid out so that those blocks run back to back on ONE die (workgroup i runs on die
 // i % 8), which then fetches the shared prefix from HBM once and serves the other rollouts from its L2.
-template <typename T, bool DIRECT>
-__global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__restrict__ q,
-                                                                    const int32_t *__restrict__ row_slot,
-                                                                    const int32_t *__restrict__ slot_len, int hq,
-                                                                    KvGeom kv, int layer, int rows, int n_splits,
-                                                                    int group, float *__restrict__ part_ml,
-                                                                    float *__restrict__ part_o,
-                                                                    T *__restrict__ out) {
-    __shared__ float sm[DEC_WAVES][16], sl[DEC_WAVES][16];
-    __shared__ float so[DEC_WAVES][16][HD];
+template <typename T, bool DIRECT, int NW>
+__global__ __launch_bounds__(64 * NW) void attention_decode_mfma_kernel(const T *__restrict__ q,
+                                                                       const int32_t *__restrict__ row_slot,
+                                                                       const int32_t *__restrict__ slot_len, int hq,
+                                                                       KvGeom kv, int layer, int rows, int n_splits,
+                                                                       int group, float *__restrict__ part_ml,
+                                                                       float *__restrict__ part_o,
+                                                                       T *__restrict__ out) {
+    constexpr int ROUND = 32 * NW;   // tokens one block consumes per pass of its waves
+    constexpr int NSLOT = 4;         // waves that hand their output to the final sum (8 waves: pairs add up first)
+    __shared__ float sm[NW][16], sl[NW][16];
+    __shared__ float so[NSLOT][16][HD];
     const int b = blockIdx.x, die = b % 8, j = b / 8;
     const int unit = (j / group) * 8 + die;              // (prompt, kv head, split)
     const int per_prompt = kv.n_kv_heads * n_splits;
@@ -315,7 +323,7 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__r
     const int kvh = (unit / n_splits) % kv.n_kv_heads, sp = unit % n_splits;
     const int slot = row_slot[r];
     const int ctx = slot_len[slot] + 1;
-    const int len = split_len(ctx, n_splits);
+    const int len = split_len(ctx, n_splits, ROUND);
     const int beg = sp * len;
     if (beg >= ctx) return;
     const int end = min(ctx, beg + len);
@@ -336,7 +344,7 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__r
     const float scale_log2 = LOG2E / sqrtf((float)HD);
     attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end, ctx - 1,
                  scale_log2, st);
-    // ---- combine the four waves
+    // ---- combine the waves
     float l = st.l;
     l += __shfl_xor(l, 16, WAVE);
     l += __shfl_xor(l, 32, WAVE);
@@ -345,31 +353,55 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__r
         sl[wave][i] = l;
     }
     __syncthreads();
+    // every wave brings its output to the block's common maximum
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int col = 4 * g + v;
         float M = sm[0][col];
 #pragma unroll
-        for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][col]);
         const float mw = sm[wave][col];
         const float fw = (mw == -INFINITY) ? 0.f : exp2f((mw - M) * scale_log2);
 #pragma unroll
-        for (int nn = 0; nn < 8; ++nn) so[wave][col][16 * nn + i] = st.o[nn][v] * fw;
+        for (int nn = 0; nn < 8; ++nn) st.o[nn][v] *= fw;
+    }
+    if (NW == 8) {   // odd waves pass their output to the even wave below them
+        if (wave % 2 == 1) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nn = 0; nn < 8; ++nn) so[wave / 2][4 * g + v][16 * nn + i] = st.o[nn][v];
+        }
+        __syncthreads();
+        if (wave % 2 == 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+#pragma unroll
+                for (int nn = 0; nn < 8; ++nn) st.o[nn][v] += so[wave / 2][4 * g + v][16 * nn + i];
+        }
+        __syncthreads();
+    }
+    if (NW == 4 || wave % 2 == 0) {
+        const int slot_w = NW == 4 ? wave : wave / 2;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+#pragma unroll
+            for (int nn = 0; nn < 8; ++nn) so[slot_w][4 * g + v][16 * nn + i] = st.o[nn][v];
     }
     __syncthreads();
-    // 16 columns x 128 values over 256 threads; a thread's values all belong to one column per pass
-    for (int e = tid; e < rep * HD; e += 256) {
+    // rep columns x 128 values over the block's threads; a thread's values all belong to one column per pass
+    for (int e = tid; e < rep * HD; e += 64 * NW) {
         const int col = e / HD, c = e % HD;
         float v = 0.f;
 #pragma unroll
-        for (int w = 0; w < DEC_WAVES; ++w) v += so[w][col][c];
+        for (int w = 0; w < NSLOT; ++w) v += so[w][col][c];
         if (DIRECT) {
             float M = sm[0][col];
 #pragma unroll
-            for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+            for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][col]);
             float L = 0.f;
 #pragma unroll
-            for (int w = 0; w < DEC_WAVES; ++w) {
+            for (int w = 0; w < NW; ++w) {
                 const float mw = sm[w][col];
                 L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
             }
@@ -383,10 +415,10 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__r
         const int col = tid;
         float M = sm[0][col];
 #pragma unroll
-        for (int w = 1; w < DEC_WAVES; ++w) M = fmaxf(M, sm[w][col]);
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][col]);
         float L = 0.f;
 #pragma unroll
-        for (int w = 0; w < DEC_WAVES; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float mw = sm[w][col];
             L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
         }
@@ -400,12 +432,13 @@ __global__ __launch_bounds__(256) void attention_decode_mfma_kernel(const T *__r
 template <typename T>
 __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32_t *__restrict__ row_slot,
                                                                      const int32_t *__restrict__ slot_len, int hq,
-                                                                     int n_splits, const float *__restrict__ part_ml,
+                                                                     int n_splits, int round,
+                                                                     const float *__restrict__ part_ml,
                                                                      const float *__restrict__ part_o,
                                                                      T *__restrict__ out) {
     const int head = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
     const int ctx = slot_len[row_slot[r]] + 1;
-    const int len = split_len(ctx, n_splits);
+    const int len = split_len(ctx, n_splits, round);
     const int ns = (ctx + len - 1) / len;            // the splits that found tokens
     const int64_t base = ((int64_t)r * hq + head) * n_splits;
     const float scale_log2 = LOG2E / sqrtf((float)HD);
@@ -420,6 +453,18 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
     out[((int64_t)r * hq + head) * HD + c] = from_f32<T>(acc / L);
 }
 
+template <typename T, int NW>
+static void decode_launch_nw(const T *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
+                             int layer, int n_splits, int group, float *part_ml, float *part_o, T *out, unsigned grid,
+                             hipStream_t s) {
+    if (n_splits == 1)
+        attention_decode_mfma_kernel<T, true, NW><<<grid, 64 * NW, 0, s>>>(q, row_slot, slot_len, hq, kv, layer, rows,
+                                                                           n_splits, group, part_ml, part_o, out);
+    else
+        attention_decode_mfma_kernel<T, false, NW><<<grid, 64 * NW, 0, s>>>(q, row_slot, slot_len, hq, kv, layer, rows,
+                                                                            n_splits, group, part_ml, part_o, out);
+}
+
 template <typename T>
 static void decode_launch(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
                           int layer, int n_splits, int group, float *scratch, void *out, hipStream_t s) {
@@ -428,12 +473,12 @@ static void decode_launch(const void *q, const int32_t *row_slot, const int32_t 
     if (group < 1 || rows % group) group = 1;
     const int units = (rows / group) * kv.n_kv_heads * n_splits;
     const unsigned grid = (unsigned)((units + 7) / 8 * 8 * group);
-    if (n_splits == 1)
-        attention_decode_mfma_kernel<T, true><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer, rows,
-                                                                   n_splits, group, part_ml, part_o, (T *)out);
+    if (decode_waves(rows, kv.n_kv_heads) == 8)
+        decode_launch_nw<T, 8>((const T *)q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, part_ml, part_o,
+                               (T *)out, grid, s);
     else
-        attention_decode_mfma_kernel<T, false><<<grid, 256, 0, s>>>((const T *)q, row_slot, slot_len, hq, kv, layer, rows,
-                                                                    n_splits, group, part_ml, part_o, (T *)out);
+        decode_launch_nw<T, 4>((const T *)q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, part_ml, part_o,
+                               (T *)out, grid, s);
 }
 
 void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
@@ -448,17 +493,18 @@ void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_s
 
 // only needed when n_splits > 1
 void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                   int n_splits, float *scratch, void *out, hipStream_t s) {
+                                   int n_kv_heads, int n_splits, float *scratch, void *out, hipStream_t s) {
     if (rows <= 0 || n_splits <= 1) return;
     const float *part_ml = scratch;
     const float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
+    const int round = 32 * decode_waves(rows, n_kv_heads);
     dim3 mgrid(hq, rows);
     if (dtype == KD_BF16)
-        attention_decode_merge_kernel<bf16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
-                                                                    (bf16_t *)out);
+        attention_decode_merge_kernel<bf16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, round, part_ml,
+                                                                    part_o, (bf16_t *)out);
     else
-        attention_decode_merge_kernel<f16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, part_ml, part_o,
-                                                                   (f16_t *)out);
+        attention_decode_merge_kernel<f16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, round, part_ml,
+                                                                   part_o, (f16_t *)out);
 }
 
 }  // namespace pc

@@ -82,12 +82,16 @@ static int bench_attention(int n, int group, int lp, int gen, int bs) {
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
     for (int g : {group, 1}) {
-        for (int l = 0; l < L; ++l) launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, 0);
+        auto layer = [&](int l) {   // the merge pass only runs when the context is split
+            launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, 0);
+            launch_attention_decode_merge(KD_F16, d_slot, d_len, n, hq, hkv, splits, scratch, out, 0);
+        };
+        for (int l = 0; l < L; ++l) layer(l);
         CK(hipDeviceSynchronize());
         const int reps = 3;
         CK(hipEventRecord(e0, 0));
         for (int r = 0; r < reps; ++r)
-            for (int l = 0; l < L; ++l) launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, 0);
+            for (int l = 0; l < L; ++l) layer(l);
         CK(hipEventRecord(e1, 0));
         CK(hipEventSynchronize(e1));
         float ms;

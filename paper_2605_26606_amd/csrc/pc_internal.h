@@ -168,7 +168,7 @@ void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_s
                                   int hq, KvGeom kv, int layer, int n_splits, int group, float *scratch, void *out,
                                   hipStream_t s);
 void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                   int n_splits, float *scratch, void *out, hipStream_t s);
+                                   int n_kv_heads, int n_splits, float *scratch, void *out, hipStream_t s);
 size_t attention_decode_scratch_floats(int max_rows, int hq, int hd);
 
 void launch_advance_len(int32_t *slot_len, const int32_t *row_slot, int rows, hipStream_t s);
