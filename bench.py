@@ -25,6 +25,30 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16
 
+# HBM traffic of one launch of the timed kernel, from the profiler's FETCH_SIZE / WRITE_SIZE counters
+# (profiles/attention_decode_c2_hbm_counters.txt).  Taken with the standalone kernel driver: same kernel,
+# grid and shapes (256 sequences in groups of 4, 256 prefix + 512 generated tokens = the mean context of
+# the launches timed here).  Each counter is scaled by what it reads for a plain 1 GiB copy.  The figure
+# is only reported while the kernel source is the one the counters were taken on.
+ATTN_COUNTERS = {"source": "paper_2605_26606_amd/csrc/attention.hip",
+                 "sha256": "45875b4c315d1dfd4ef59c2d193d17fe6590fb93923f83e5c19cfb44f56ea606",
+                 "seqs": 256, "prompt_len": 256, "mean_generated": 512,
+                 "fetch_kib": 74218.1, "fetch_scale": 1048576.0 / 524300.5,
+                 "write_kib": 768.0, "write_scale": 1048576.0 / 1048576.0}
+
+
+def counter_traffic_bytes(n_seqs, prompt_len, mean_generated):
+    import hashlib
+    c = ATTN_COUNTERS
+    try:
+        with open(os.path.join(ROOT, c["source"]), "rb") as f:
+            same = hashlib.sha256(f.read()).hexdigest() == c["sha256"]
+    except OSError:
+        same = False
+    if not same or (n_seqs, prompt_len) != (c["seqs"], c["prompt_len"]) or abs(mean_generated - c["mean_generated"]) > 1:
+        return None
+    return int((c["fetch_kib"] * c["fetch_scale"] + c["write_kib"] * c["write_scale"]) * 1024)
+
 
 def decode_bytes_per_step(model, n_prompts_active, prompt_len, n_seqs, t):
     """Algorithmic HBM bytes of decode step t (the step that feeds generated token t-1):
@@ -142,8 +166,11 @@ def main():
         bracket_ms = empty_ms / empty_pairs if empty_pairs else 0.0   # what an event pair around nothing reads
         avg_ms = max(attn_ms / attn_launches - bracket_ms, 1e-6)
         achieved = attn_bytes / attn_launches / (avg_ms * 1e-3) / 1e9
-        roof = {"kernel": "attention_decode_mfma_kernel<f16, direct> (pilot pass, 256 sequences)", "bound": "hbm", "achieved": round(achieved, 1),
-                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+        pilot_t = [t for (which, t, _, _) in timed_steps if which == "pilot"]
+        traffic = counter_traffic_bytes(P * wl.n_pilot, Lp, sum(pilot_t) / max(1, len(pilot_t))) \
+            if len(pilot_t) == len(timed_steps) else None
+        roof = {"kernel": "attention_decode_mfma_kernel<f16, direct, 4 waves> (pilot pass, 256 sequences)", "bound": "hbm", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(avg_ms * 1e3, 2), "event_bracket_us": round(bracket_ms * 1e3, 2),
                 "launches_timed": int(attn_launches),
                 "bytes_per_launch": int(attn_bytes / attn_launches)}

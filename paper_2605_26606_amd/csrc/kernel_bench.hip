@@ -3,7 +3,9 @@
 // workload, with synthetic cache contents, and times them with HIP events.  Used for tuning and for
 // hardware-counter runs (rocprofv3 --pmc), which need a plain process without HIP graphs.
 //
-//   kernel_bench attn [n_seqs group prompt_len gen_len block_size]   (defaults 256 4 256 512 64)
+//   kernel_bench attn [n_seqs group prompt_len gen_len block_size grouped_only event_study]   (defaults 256 4 256 512 64 0 0)
+//       event_study: also brackets single launches with an event pair, as the library's per-launch timing does,
+//       next to pairs around nothing / one / two empty kernels and around two launches
 //   kernel_bench gemm
 //   kernel_bench copy                                       (a plain 1 GiB copy: the counters' known-size reference)
 #include <stdio.h>
@@ -40,7 +42,9 @@ __global__ void copy_kernel(const float4 *__restrict__ src, float4 *__restrict__
     if (i < n) dst[i] = src[i];
 }
 
-static int bench_attention(int n, int group, int lp, int gen, int bs) {
+__global__ void null_kernel() {}
+
+static int bench_attention(int n, int group, int lp, int gen, int bs, bool grouped_only, bool event_study) {
     const int L = 28, hq = 12, hkv = 2, hd = 128;
     const int P = n / group, ctx = lp + gen;
     const int pre_blocks = lp / bs, own_blocks = (ctx + bs - 1) / bs - pre_blocks, per_slot = pre_blocks + own_blocks;
@@ -82,6 +86,7 @@ static int bench_attention(int n, int group, int lp, int gen, int bs) {
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
     for (int g : {group, 1}) {
+        if (grouped_only && g != group) continue;
         auto layer = [&](int l) {   // the merge pass only runs when the context is split
             launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, 0);
             launch_attention_decode_merge(KD_F16, d_slot, d_len, n, hq, hkv, splits, scratch, out, 0);
@@ -103,6 +108,36 @@ static int bench_attention(int n, int group, int lp, int gen, int bs) {
                "(per-sequence bytes %.1f MB -> %.0f GB/s)  %s\n",
                n, group, g, bs, lp, gen, splits, us, alg / 1e6, alg / us / 1e3, raw / 1e6, raw / us / 1e3,
                hipGetErrorString(hipGetLastError()));
+        if (event_study && g == group) {
+            // what an event pair reads around k launches of a kernel, averaged
+            auto pair_us = [&](int k, bool attn, double *out_us) -> int {
+                const int reps = 3;
+                double tot = 0;
+                for (int r = 0; r < reps; ++r)
+                    for (int l = 0; l < L; ++l) {
+                        CK(hipEventRecord(e0, 0));
+                        for (int c = 0; c < k; ++c) {
+                            if (attn) layer(l);
+                            else null_kernel<<<1, 64>>>();
+                        }
+                        CK(hipEventRecord(e1, 0));
+                        CK(hipEventSynchronize(e1));
+                        float one;
+                        CK(hipEventElapsedTime(&one, e0, e1));
+                        tot += one;
+                    }
+                *out_us = tot * 1e3 / (reps * L);
+                return 0;
+            };
+            double p0, n1, n2, a1, a2;
+            if (pair_us(0, false, &p0) || pair_us(1, false, &n1) || pair_us(2, false, &n2) || pair_us(1, true, &a1) ||
+                pair_us(2, true, &a2))
+                return 1;
+            printf("event pair around: nothing %.2f us, one empty kernel %.2f us, two empty kernels %.2f us, "
+                   "one attention launch %.2f us, two attention launches %.2f us\n", p0, n1, n2, a1, a2);
+            printf("  attention launch: %.2f us by (pair - empty pair), %.2f us by (two launches - one launch)\n", a1 - p0,
+                   a2 - a1);
+        }
     }
     return 0;
 }
@@ -177,7 +212,7 @@ int main(int argc, char **argv) {
             fprintf(stderr, "bad sizes\n");
             return 2;
         }
-        return bench_attention(n, g, lp, gen, bs);
+        return bench_attention(n, g, lp, gen, bs, argc > 7 && atoi(argv[7]) != 0, argc > 8 && atoi(argv[8]) != 0);
     }
     if (!strcmp(what, "gemm")) return bench_gemm();
     if (!strcmp(what, "copy")) return bench_copy();
