@@ -25,21 +25,29 @@ def _seq_uids(prompt_uids: np.ndarray, rollout_indices) -> np.ndarray:
 def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_logits: torch.Tensor,
              seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
              eos_logit_bias: float = 0.0, stream=None, keep_logits_rows: Optional[np.ndarray] = None,
-             poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None):
+             poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None,
+             compact: bool = True):
     """Samples one completion per entry of `handles` (prompt handles, one per
     sequence).  Token 0 comes from the prompt's prefill logits
     (first_logits[logit_rows[i]]); tokens 1.. from decode steps.
 
+    With an EOS id the finished flags are read back every `poll_every` steps;
+    when enough sequences have stopped (`compact`), they are released and the
+    decode batch shrinks to the live ones (ragged stop), and the pass ends as
+    soon as none is left.
+
     Returns dict(tokens [n, T] int32 device (eos_id-padded after the end when
-    EOS is on), lengths [n] int32 device, steps_run, logits (optional: list per
-    step of the requested rows, for parity tests))."""
+    EOS is on), lengths [n] int32 device, steps_run, rows_decoded (sum of the
+    batch sizes of the decode steps), logits / logits_rows (optional: per step
+    the logits of the requested rows that were still in the batch, and which
+    rows those are; for parity tests))."""
     dev = first_logits.device
     n = len(handles)
     V = ctx.vocab
     T = int(new_tokens)
-    hist = torch.zeros((T, max(n, 1)), dtype=torch.int32, device=dev)
+    hist = torch.full((T, max(n, 1)), eos_id if eos_id >= 0 else 0, dtype=torch.int32, device=dev)
     out = dict(tokens=hist[:, :n].t().contiguous(), lengths=torch.zeros(n, dtype=torch.int32, device=dev),
-               steps_run=0, logits=[])
+               steps_run=0, rows_decoded=0, logits=[], logits_rows=[])
     if n == 0 or T == 0:
         return out
     seqs = B.pc_fork(ctx, handles, T, stream)
@@ -49,27 +57,55 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
     logits = torch.empty((n, V), dtype=torch.float32, device=dev)
     finished = torch.zeros(n, dtype=torch.uint8, device=dev) if eos_id >= 0 else None
     keep = None if keep_logits_rows is None else torch.as_tensor(keep_logits_rows, dtype=torch.long, device=dev)
+    keep_mask = None
+    if keep is not None:
+        keep_mask = torch.zeros(n, dtype=torch.bool, device=dev)
+        keep_mask[keep] = True
+    active = None                      # original index of each batch row; None = identity
     B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, None,
                 finished, stream)
     hist[0, :n].copy_(cur)
     if keep is not None:
         out["logits"].append(first_logits[rows_d.long()[keep]].clone())
-    steps = 1
+        out["logits_rows"].append(keep.clone())
+    steps, rows_decoded = 1, 0
     for t in range(1, T):
-        if finished is not None and t % poll_every == 0 and bool(finished.all().item()):
-            hist[t:, :n] = eos_id
-            break
+        if finished is not None and t % poll_every == 0:
+            fin = finished.cpu().numpy().astype(bool)          # the pass's only periodic read-back
+            if fin.all():
+                break
+            if compact and fin.sum() >= max(1, len(fin) // 16):
+                alive = np.nonzero(~fin)[0]
+                B.pc_release(ctx, seqs[fin], 0)
+                seqs = np.ascontiguousarray(seqs[alive])
+                alive_d = torch.from_numpy(alive).to(dev)
+                active = alive_d if active is None else active[alive_d]
+                cur = cur[alive_d].contiguous()
+                uid_d = uid_d[alive_d].contiguous()
+                finished = finished[alive_d].contiguous()
+                logits = logits[:len(alive)]
+        m = len(seqs)
         if time_every > 0 and t % time_every == time_every // 2:
             # this step runs eagerly with HIP events around every launch of one kernel class
             B.pc_set_option(ctx, B.PC_OPT_TIME_NEXT_STEP, time_class)
             if timed_steps is not None:
-                timed_steps.append((t, n))
+                timed_steps.append((t, m))
         B.pc_decode_step(ctx, seqs, cur, logits, stream)
+        rows_decoded += m
         if keep is not None:
-            out["logits"].append(logits[keep].clone())
-        B.pc_sample(logits, None, n, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, None,
+            if active is None:
+                out["logits"].append(logits[keep].clone())
+                out["logits_rows"].append(keep.clone())
+            else:
+                sel = keep_mask[active]
+                out["logits"].append(logits[sel].clone())
+                out["logits_rows"].append(active[sel].clone())
+        B.pc_sample(logits, None, m, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, None,
                     finished, stream)
-        hist[t, :n].copy_(cur)
+        if active is None:
+            hist[t, :n].copy_(cur)
+        else:
+            hist[t].index_copy_(0, active, cur)
         steps += 1
     B.pc_release(ctx, seqs, 0)
     toks = hist[:, :n].t().contiguous()
@@ -80,7 +116,7 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
         lengths = first.to(torch.int32)
     else:
         lengths = torch.full((n,), T, dtype=torch.int32, device=dev)
-    out.update(tokens=toks, lengths=lengths, steps_run=steps)
+    out.update(tokens=toks, lengths=lengths, steps_run=steps, rows_decoded=rows_decoded)
     return out
 
 

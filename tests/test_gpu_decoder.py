@@ -62,7 +62,7 @@ def _teacher_forced(model, w, prompt, gen_tokens, gpu_logits, uid, seed, tempera
 
 
 def _run_generate(model, w_cpu, prompts_list, G, T, seed, ctx_kw, opts=(), temperature=1.0, stream=True,
-                  eos_id=-1, bias=0.0):
+                  eos_id=-1, bias=0.0, poll_every=64, compact=True):
     import paper_2605_26606_amd as pc
     ctx = make_ctx(model, w_cpu, **ctx_kw)
     for o, v in opts:
@@ -79,14 +79,18 @@ def _run_generate(model, w_cpu, prompts_list, G, T, seed, ctx_kw, opts=(), tempe
         uids = (rows.astype(np.int64) * 65536 + np.tile(np.arange(G), P))
         n = P * G
         g = pc.generate(ctx, handles[rows], rows, last, uids, T, temperature, seed, eos_id, bias,
-                        keep_logits_rows=np.arange(n))
+                        keep_logits_rows=np.arange(n), poll_every=poll_every, compact=compact)
         pc.pc_release(ctx, handles, 1)
     torch.cuda.synchronize()
     free, total = pc.pc_kv_blocks(ctx)
     assert free == total, "released everything, yet %d of %d blocks are free" % (free, total)
-    logits = torch.stack(g["logits"]).cpu().numpy()          # [steps, n, V]
+    # [steps, n, V]; rows that had left the batch (ragged stop) stay NaN
+    logits = np.full((len(g["logits"]), n, model.vocab), np.nan, dtype=np.float32)
+    for t, (lg, lr) in enumerate(zip(g["logits"], g["logits_rows"])):
+        logits[t, lr.cpu().numpy()] = lg.cpu().numpy()
     out = dict(tokens=g["tokens"].cpu().numpy(), lengths=g["lengths"].cpu().numpy(), logits=logits,
-               last=last.cpu().numpy(), uids=uids, rows=rows)
+               last=last.cpu().numpy(), uids=uids, rows=rows, steps_run=g["steps_run"],
+               rows_decoded=g["rows_decoded"])
     ctx.close()
     return out
 
@@ -216,6 +220,33 @@ def test_eos_stops_sequences_fp32():
         if L < 24:
             assert out["tokens"][i, L - 1] == eos and (out["tokens"][i, L:] == eos).all()
     _check(m, w, prompts, out, 3, 1e-4, range(16), eos_id=eos, bias=bias)
+
+
+@pytest.mark.parametrize("name", ["fp32", "f16"])
+def test_ragged_stop_shrinks_the_batch(name):
+    # sequences that hit EOS leave the decode batch at the next poll; what the others generate is unchanged
+    m = C1.model if name == "fp32" else BF
+    say("ragged stop, %s: 4 prompts x 8 rollouts, 72 new tokens, poll every 8 steps" % name)
+    w = workloads.perturb_norm_gains(workloads.make_weights(m, 1), 7)
+    prompts = list(workloads.make_prompts(4, 20, m.vocab, 2))
+    eos = workloads.make_eos_id(m.vocab, 4)
+    bias = math.log(m.vocab / 12.0)             # hazard about 1/12 per step
+    kw = dict(block_size=32, kv_pool_bytes=64 << 20, max_slots=96, max_ctx=128, max_batch_rows=128)
+    a = _run_generate(m, w, prompts, 8, 72, 3, kw, eos_id=eos, bias=bias, poll_every=8, compact=True)
+    b = _run_generate(m, w, prompts, 8, 72, 3, kw, eos_id=eos, bias=bias, poll_every=8, compact=False)
+    lens = a["lengths"]
+    say("lengths %s; batch rows decoded %d with compaction, %d without" % (sorted(lens.tolist()), a["rows_decoded"],
+                                                                        b["rows_decoded"]))
+    assert (lens < 72).sum() >= 16 and a["rows_decoded"] < b["rows_decoded"]
+    for i in range(32):
+        L = int(lens[i])
+        assert (a["tokens"][i, :L - 1] != eos).all()
+        if L < 72:
+            assert a["tokens"][i, L - 1] == eos and (a["tokens"][i, L:] == eos).all()
+        assert not np.isnan(a["logits"][:L, i]).any()      # every token was sampled from recorded logits
+    if name == "fp32":   # the plain-ALU kernels treat a row the same whatever else is in the batch
+        assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(lens, b["lengths"])
+    _check(m, w, prompts, a, 3, 1e-4 if name == "fp32" else 2e-2, range(0, 32, 3), eos_id=eos, bias=bias)
 
 
 def test_error_paths_leave_state_unchanged():
