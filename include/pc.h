@@ -218,6 +218,76 @@ pc_status pc_select_commit(const float *p_hat, int32_t P, float p_lower, float p
 pc_status pc_advantages(const float *rewards, const int32_t *group_off, int32_t P, float eps, float *adv,
                         float *mu, float *sigma, void *stream);
 
+/* ---------------------------------------------------------------------------
+ * Multi-step scheduling (Algorithm 1 with the optimisations of Section 3.4:
+ * replay buffer for pilot survivors, maximum pilot-to-commit delay d,
+ * eviction of solved prompts from the dataset pool).  Host-side bookkeeping:
+ * every pointer below is a HOST pointer, nothing touches the GPU, no stream.
+ *
+ * One training step t is: one or more pc_sched_pilot calls (one per sampling
+ * batch; a second call in the same step is the "second sampling round" of
+ * Section 5.4), then one pc_sched_commit call.
+ * ------------------------------------------------------------------------- */
+typedef struct pc_sched pc_sched;
+
+typedef struct {
+    float p_lower, p_upper, p_solve; /* Section 3.3 filter bounds (inclusive), Algorithm 1 eviction threshold (>=) */
+    int32_t b_t;                     /* training batch size: prompts committed per step, > 0 */
+    int32_t max_delay;               /* d >= 0 (Section 4.2: 4): a survivor of step t0 can be committed at steps t0 .. t0+d */
+} pc_sched_config;
+
+#define PC_SCHED_STEP 0            /* t: commits done so far */
+#define PC_SCHED_BUFFERED_NOW 1    /* entries waiting in the replay buffer */
+#define PC_SCHED_PILOT_BATCHES 2   /* pc_sched_pilot calls */
+#define PC_SCHED_PROMPTS_SEEN 3
+#define PC_SCHED_BUFFERED 4        /* survivors ever put into the buffer */
+#define PC_SCHED_COMMITTED 5
+#define PC_SCHED_AGED_OUT 6
+#define PC_SCHED_EVICTIONS 7       /* prompts flagged p_hat >= p_solve */
+#define PC_SCHED_SHORT_STEPS 8     /* steps that committed fewer than b_t prompts */
+#define PC_SCHED_MULTI_ROUND_STEPS 9 /* steps with more than one sampling batch */
+#define PC_SCHED_NSTATS 10
+
+pc_status pc_sched_create(const pc_sched_config *cfg, pc_sched **out);
+pc_status pc_sched_destroy(pc_sched *s);
+
+/* Pilot outcome of one sampling batch at the current step (Algorithm 1:
+ * filter B' = {q : p_lower <= p_hat <= p_upper}, eviction {q : p_hat >=
+ * p_solve}, R <- R u B').  Comparisons are taken in fp32, as pc_select_commit
+ * takes them.  Survivors enter the buffer in batch order, stamped with t.
+ *   prompt_uid  host int64 [n]
+ *   tag         host int64 [n] or NULL (then 0): carried with the entry and
+ *               handed back on commit / age-out (e.g. the caller's handle of
+ *               the stored pilot rollouts and prefix KV)
+ *   p_hat       host fp32 [n]
+ *   cls, evict  host uint8 [n] or NULL, as in pc_select_commit
+ *   counts      host int32 [4] or NULL: buffered, evicted, too easy, too hard */
+pc_status pc_sched_pilot(pc_sched *s, const int64_t *prompt_uid, const int64_t *tag, const float *p_hat,
+                         int32_t n, uint8_t *cls, uint8_t *evict, int32_t *counts);
+
+/* Commit selection of the current step (Algorithm 1, Commit lines), then the
+ * age-out and t <- t+1.  Up to b_t entries leave the buffer: the survivors of
+ * the current step first, in batch order (Section 3.4: only a step's excess is
+ * buffered, the buffer fills a step that came up short); then older ones,
+ * oldest step first, in insertion order.  Entries that could not be committed
+ * by step t0+d any more (t+1-t0 > d) are dropped and reported.
+ *   uid_out, tag_out  host int64 [b_t]; age_out host int32 [b_t] (t - t0)
+ *   n_selected        host int32 [1]
+ *   aged_uid_out, aged_tag_out  host int64 [aged_cap] or NULL; n_aged host
+ *               int32 [1] or NULL.  If more entries age out than aged_cap
+ *               holds the call fails with PC_ERR_INVALID_ARG and changes
+ *               nothing (PC_SCHED_BUFFERED_NOW is always enough). */
+pc_status pc_sched_commit(pc_sched *s, int64_t *uid_out, int64_t *tag_out, int32_t *age_out,
+                          int32_t *n_selected, int64_t *aged_uid_out, int64_t *aged_tag_out, int32_t aged_cap,
+                          int32_t *n_aged);
+
+/* out[i] = 1 if prompt_uid[i] has been evicted from the pool (Section 3.4:
+ * not sampled again in later epochs).  Host arrays. */
+pc_status pc_sched_evicted(const pc_sched *s, const int64_t *prompt_uid, int32_t n, uint8_t *out);
+
+/* out: host int64 [PC_SCHED_NSTATS], indexed by the PC_SCHED_* constants. */
+pc_status pc_sched_stats(const pc_sched *s, int64_t *out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -42,6 +42,15 @@ class _Weights(C.Structure):
            ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")]
 
 
+class _SchedConfig(C.Structure):
+    _fields_ = [("p_lower", C.c_float), ("p_upper", C.c_float), ("p_solve", C.c_float), ("b_t", C.c_int32),
+                ("max_delay", C.c_int32)]
+
+
+PC_SCHED_STATS = ("step", "buffered_now", "pilot_batches", "prompts_seen", "buffered", "committed", "aged_out",
+                  "evictions", "short_steps", "multi_round_steps")
+
+
 class _CacheConfig(C.Structure):
     _fields_ = [("block_size", C.c_int32), ("kv_pool_bytes", C.c_int64), ("max_slots", C.c_int32),
                 ("max_ctx", C.c_int32), ("max_batch_rows", C.c_int32)]
@@ -75,6 +84,12 @@ def library() -> C.CDLL:
             "pc_group_stats": [vp, vp, i32, vp, vp, vp, vp, vp],
             "pc_select_commit": [vp, i32, f32, f32, f32, i32, vp, vp, vp, vp, vp, vp],
             "pc_advantages": [vp, vp, i32, f32, vp, vp, vp, vp],
+            "pc_sched_create": [C.POINTER(_SchedConfig), C.POINTER(vp)],
+            "pc_sched_destroy": [vp],
+            "pc_sched_pilot": [vp, vp, vp, vp, i32, vp, vp, vp],
+            "pc_sched_commit": [vp, vp, vp, vp, vp, vp, vp, i32, vp],
+            "pc_sched_evicted": [vp, vp, i32, vp],
+            "pc_sched_stats": [vp, vp],
         }
         for name, args in sigs.items():
             fn = getattr(lib, name)
@@ -276,3 +291,59 @@ def pc_advantages(rewards: torch.Tensor, group_off: torch.Tensor, eps: float, ad
     _check(library().pc_advantages(_dev(rewards, torch.float32, "rewards"), _dev(group_off, torch.int32, "group_off"),
                                    P, float(eps), _dev(adv, torch.float32, "adv"), _dev(mu, torch.float32, "mu"),
                                    _dev(sigma, torch.float32, "sigma"), _stream_ptr(stream)))
+
+
+class Scheduler:
+    """Multi-step scheduling state (pc_sched_*): host arrays in, host arrays out."""
+
+    def __init__(self, p_lower: float, p_upper: float, p_solve: float, b_t: int, max_delay: int):
+        cfg = _SchedConfig(float(p_lower), float(p_upper), float(p_solve), int(b_t), int(max_delay))
+        h = C.c_void_p()
+        _check(library().pc_sched_create(C.byref(cfg), C.byref(h)))
+        self.handle = h
+        self.b_t = int(b_t)
+
+    def close(self):
+        if self.handle is not None:
+            library().pc_sched_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def pilot(self, prompt_uid, tag, p_hat):
+        """One sampling batch at the current step -> (cls u8 [n], evict u8 [n], counts i32 [4])."""
+        uid = np.ascontiguousarray(prompt_uid, dtype=np.int64)
+        tg = None if tag is None else np.ascontiguousarray(tag, dtype=np.int64)
+        ph = np.ascontiguousarray(p_hat, dtype=np.float32)
+        n = len(uid)
+        if len(ph) != n or (tg is not None and len(tg) != n):
+            raise ValueError("prompt_uid, tag and p_hat must have the same length")
+        cls, ev, counts = np.zeros(max(n, 1), np.uint8), np.zeros(max(n, 1), np.uint8), np.zeros(4, np.int32)
+        _check(library().pc_sched_pilot(self.handle, uid.ctypes.data, None if tg is None else tg.ctypes.data,
+                                        ph.ctypes.data, n, cls.ctypes.data, ev.ctypes.data, counts.ctypes.data))
+        return cls[:n], ev[:n], counts
+
+    def commit(self):
+        """Commit selection, age-out, t <- t+1 -> ((uid, tag, age), (aged uid, aged tag))."""
+        cap = int(self.stats()["buffered_now"])
+        uid, tg, age = np.zeros(self.b_t, np.int64), np.zeros(self.b_t, np.int64), np.zeros(self.b_t, np.int32)
+        auid, atg = np.zeros(max(cap, 1), np.int64), np.zeros(max(cap, 1), np.int64)
+        k, a = C.c_int32(0), C.c_int32(0)
+        _check(library().pc_sched_commit(self.handle, uid.ctypes.data, tg.ctypes.data, age.ctypes.data,
+                                         C.addressof(k), auid.ctypes.data, atg.ctypes.data, cap, C.addressof(a)))
+        return (uid[:k.value], tg[:k.value], age[:k.value]), (auid[:a.value], atg[:a.value])
+
+    def evicted(self, prompt_uid) -> np.ndarray:
+        uid = np.ascontiguousarray(prompt_uid, dtype=np.int64)
+        out = np.zeros(max(len(uid), 1), np.uint8)
+        _check(library().pc_sched_evicted(self.handle, uid.ctypes.data, len(uid), out.ctypes.data))
+        return out[:len(uid)]
+
+    def stats(self) -> dict:
+        out = np.zeros(len(PC_SCHED_STATS), np.int64)
+        _check(library().pc_sched_stats(self.handle, out.ctypes.data))
+        return dict(zip(PC_SCHED_STATS, out.tolist()))
