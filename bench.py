@@ -98,6 +98,9 @@ def main():
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps eagerly (for counter runs: the profiler's counter mode and HIP graphs "
                          "do not go together)")
+    ap.add_argument("--binding-steps", type=int, default=4,
+                    help="after the timed steps, also run this many sampling batches through the bound pipeline "
+                         "(commit pass of step t-1 in one decode batch with the pilot pass of step t); 0 = skip")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size reference of the counter runs)")
     args = ap.parse_args()
@@ -121,10 +124,13 @@ def main():
     prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, m.vocab, wl.seed_prompts)
     uids = workloads.make_prompt_uids(wl.n_prompts)
     P, Lp, T = wl.n_prompts, wl.prompt_len, wl.new_tokens
-    n_max = P * max(wl.n_pilot, wl.n_commit)
-    kv_tokens = P * Lp + n_max * (T + 64) + 4096
+    bound = args.binding_steps > 0
+    # unbound: one pass at a time; bound: pilot and commit sequences decode together, two batches of prompts alive
+    n_max = P * (wl.n_pilot + wl.n_commit) if bound else P * max(wl.n_pilot, wl.n_commit)
+    n_prompts_alive = 2 * P if bound else P
+    kv_tokens = n_prompts_alive * Lp + n_max * (T + 64) + 4096
     ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
-                     max_slots=P + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
+                     max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
     if args.no_graph:
         pc.pc_set_option(ctx, pc.PC_OPT_USE_GRAPH, 0)
     cu = (np.arange(P + 1) * Lp).astype(np.int32)
@@ -204,6 +210,34 @@ def main():
         "prefill": {"ms": round(prefill_ms, 2), "TFLOPs": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9, 1),
                     "frac_mfma": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
+    if bound:
+        # the same work re-scheduled (Section 3.4 binding): fresh prompts every step, commit pass of the previous
+        # step's kept prompts in the same decode batch as this step's pilot pass; one extra pass drains the last commit
+        batches = []
+        for b in range(args.binding_steps):
+            pr = workloads.make_prompts(P, Lp, m.vocab, wl.seed_prompts + 100 + b)
+            batches.append((torch.from_numpy(pr.reshape(-1).astype(np.int32)).to(dev),
+                            workloads.make_prompt_uids(P, first=10000 * (b + 1))))
+        with torch.cuda.stream(stream):
+            pipe = pc.BoundPipeline(ctx, wl, wl.seed_sampler + 7, eos_id)
+            torch.cuda.synchronize()
+            marks, info = [time.perf_counter()], []
+            for tk, uid_b in batches + [(None, None)]:
+                o = pipe.step(tk, None if tk is None else cu, uid_b,
+                              p_q=p_q, reward_u=ru) if tk is not None else pipe.step(None, None, None)
+                torch.cuda.synchronize()
+                marks.append(time.perf_counter())
+                if o is not None:
+                    info.append((o["rows"], o["tokens_generated"], marks[-1] - marks[-2]))
+            pipe.close()
+        tot_tok = sum(i[1] for i in info)
+        mid = info[1:-1] if len(info) > 2 else info
+        result["binding"] = {
+            "value": round(tot_tok / (marks[-1] - marks[0]), 1), "unit": "tokens/s",
+            "sampling_batches": args.binding_steps, "passes": len(info),
+            "steady_tokens_per_s": round(sum(i[1] for i in mid) / sum(i[2] for i in mid), 1),
+            "rows_per_pass": [i[0] for i in info], "ms_per_pass": [round(i[2] * 1e3, 1) for i in info],
+            "note": "ramp-up (pilot only) and drain (commit only) passes included in value, excluded from steady"}
     if args.calibrate_copy:   # rocprofv3 --pmc runs scale FETCH_SIZE / WRITE_SIZE by what this copy reads
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)

@@ -10,4 +10,4 @@ from .binding import (  # noqa: F401
     pc_timing_read, PC_OPT_USE_GRAPH, PC_OPT_FORCE_SIMT, PC_OPT_TIME_NEXT_STEP, PC_KERNEL_ATTN_DECODE,
     PC_KERNEL_GEMM_QKV, PC_KERNEL_GEMM_WO, PC_KERNEL_GEMM_GATE_UP, PC_KERNEL_GEMM_DOWN, PC_KERNEL_GEMM_LM_HEAD,
 )
-from .rollout import pilot_commit_step, generate  # noqa: F401
+from .rollout import pilot_commit_step, generate, BoundPipeline  # noqa: F401

@@ -330,7 +330,8 @@ class Scheduler:
     def commit(self):
         """Commit selection, age-out, t <- t+1 -> ((uid, tag, age), (aged uid, aged tag))."""
         cap = int(self.stats()["buffered_now"])
-        uid, tg, age = np.zeros(self.b_t, np.int64), np.zeros(self.b_t, np.int64), np.zeros(self.b_t, np.int32)
+        kmax = max(1, min(self.b_t, cap))          # never more than the buffer holds
+        uid, tg, age = np.zeros(kmax, np.int64), np.zeros(kmax, np.int64), np.zeros(kmax, np.int32)
         auid, atg = np.zeros(max(cap, 1), np.int64), np.zeros(max(cap, 1), np.int64)
         k, a = C.c_int32(0), C.c_int32(0)
         _check(library().pc_sched_commit(self.handle, uid.ctypes.data, tg.ctypes.data, age.ctypes.data,

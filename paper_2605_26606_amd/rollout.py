@@ -232,3 +232,134 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
                 commit_rewards=commit_r.view(K, ncom), union_rewards=union_r, advantages=adv.view(K, npil + ncom),
                 mu=mu[:K], sigma=sigma[:K], rollouts=P * npil + K * ncom, tokens_generated=n_tok,
                 decode_steps=g["steps_run"] + gc["steps_run"])
+
+
+class BoundPipeline:
+    """Pilot/commit binding (Section 3.4) on one GPU: the commit rollouts of the
+    prompts selected at step t-1 and the pilot rollouts of the sampling batch
+    of step t are generated in ONE decode batch, so the commit pass, which on
+    its own is too small to amortise the weight stream, rides along with the
+    pilot pass.  Selection between the steps goes through the library's
+    scheduler (replay buffer, cap b_t, maximum delay d, eviction).  The prefix
+    KV and the last-row logits of a kept prompt stay alive until its commit
+    pass has run; everything else is released as soon as it is decided.
+
+    The policy (weights) is the same for every step here, so binding changes
+    the schedule, not the results: every sequence gets the tokens it would get
+    in an unbound step (same uid, same Philox stream, same logits up to the
+    kernels' batch-size-dependent summation order)."""
+
+    def __init__(self, ctx: B.Context, wl, seed: int, eos_id: int = -1, eos_logit_bias: float = 0.0,
+                 max_delay: int = 0, b_t: Optional[int] = None, eps: float = 1e-6):
+        self.ctx, self.wl, self.seed, self.eos_id, self.eos_bias, self.eps = ctx, wl, seed, eos_id, eos_logit_bias, eps
+        cap = b_t if b_t is not None else wl.b_t
+        self.sched = B.Scheduler(wl.p_lower, wl.p_upper, wl.p_solve, cap if cap and cap > 0 else (1 << 30) - 1,
+                                 max_delay)
+        self.entries = {}          # tag -> dict(handle, uid, logits [V] device, pilot_r [n_pilot] device, tokens)
+        self.pending = []          # tags selected for the commit pass of the next step
+        self.next_tag = 0
+        self.step_no = 0
+
+    def close(self):
+        for e in self.entries.values():
+            B.pc_release(self.ctx, np.array([e["handle"]], np.int32), 1)
+        self.entries.clear()
+        self.pending = []
+        self.sched.close()
+
+    def step(self, prompt_tokens: Optional[torch.Tensor], cu_lens: Optional[np.ndarray],
+             prompt_uids: Optional[np.ndarray], p_q: Optional[np.ndarray] = None,
+             reward_u: Optional[np.ndarray] = None, stream=None):
+        """Runs the pilot pass of this sampling batch (None: no new batch, drain
+        only) together with the commit pass of the prompts selected at the
+        previous step.  Returns a dict: pilot_* of this batch, commit_* /
+        advantages of the prompts whose commit pass just ran."""
+        ctx, wl = self.ctx, self.wl
+        npil, ncom, T, V = wl.n_pilot, wl.n_commit, wl.new_tokens, ctx.vocab
+        P = 0 if cu_lens is None else len(cu_lens) - 1
+        com = [self.entries[t] for t in self.pending]
+        K = len(com)
+        if P == 0 and K == 0:
+            return None
+        dev = prompt_tokens.device if P else com[0]["logits"].device
+        uids = np.zeros(0, np.int64) if P == 0 else np.asarray(prompt_uids, dtype=np.int64)
+        handles = np.zeros(0, np.int32)
+        parts = []
+        if P:
+            last_logits = torch.empty((P, V), dtype=torch.float32, device=dev)
+            handles = B.pc_prefill_shared(ctx, prompt_tokens, cu_lens, last_logits, stream)
+            parts.append(last_logits)
+        if K:
+            parts.append(torch.stack([e["logits"] for e in com]))
+        first_logits = parts[0] if len(parts) == 1 else torch.cat(parts)
+        # ---- one decode batch: pilot sequences of this batch, then commit sequences of the selected prompts
+        prow = np.repeat(np.arange(P, dtype=np.int32), npil)
+        crow = np.repeat(np.arange(K, dtype=np.int32), ncom)
+        seq_handles = np.concatenate([handles[prow], np.array([e["handle"] for e in com], np.int32)[crow]])
+        logit_rows = np.concatenate([prow, P + crow]).astype(np.int32)
+        c_uids = np.array([e["uid"] for e in com], np.int64)
+        seq_uids = np.concatenate([_seq_uids(uids, range(npil)), _seq_uids(c_uids, range(npil, npil + ncom))])
+        g = generate(ctx, seq_handles, logit_rows, first_logits, seq_uids, T, wl.temperature, self.seed, self.eos_id,
+                     self.eos_bias, stream)
+        n_p = P * npil
+        out = dict(step=self.step_no, rows=n_p + K * ncom, decode_steps=g["steps_run"],
+                   tokens_generated=int(g["lengths"].sum().item()))
+        uid_d = torch.from_numpy(uids).to(dev)
+        # ---- pilot outcome of this batch -> scheduler
+        if P:
+            prow_d = torch.from_numpy(prow).to(dev).long()
+            pq_d = None if p_q is None else torch.from_numpy(np.asarray(p_q, np.float32)).to(dev)
+            ru_d = None if reward_u is None else torch.from_numpy(np.asarray(reward_u, np.float32)).to(dev)
+            pilot_r = synthetic_rewards(wl.reward, g["tokens"][:n_p], g["lengths"][:n_p], uid_d[prow_d],
+                                        None if pq_d is None else pq_d[prow_d],
+                                        None if ru_d is None else ru_d[:, :npil].reshape(-1))
+            off = torch.arange(P + 1, dtype=torch.int32, device=dev) * npil
+            p_hat = torch.empty(P, dtype=torch.float32, device=dev)
+            B.pc_group_stats(pilot_r, off, None, None, p_hat, None, stream)
+            p_hat_h = p_hat.cpu().numpy()                    # the step's read-back: P floats
+            tags = np.arange(self.next_tag, self.next_tag + P, dtype=np.int64)
+            self.next_tag += P
+            cls, evict, counts = self.sched.pilot(uids, tags, p_hat_h)
+            for q in range(P):
+                if cls[q] == 1:
+                    self.entries[int(tags[q])] = dict(
+                        handle=int(handles[q]), uid=int(uids[q]), logits=last_logits[q],
+                        pilot_r=pilot_r[q * npil:(q + 1) * npil], pilot_tokens=g["tokens"][q * npil:(q + 1) * npil],
+                        reward_u=None if reward_u is None else np.asarray(reward_u[q], np.float32),
+                        p_q=None if p_q is None else float(p_q[q]))
+            dropped = handles[cls != 1]
+            if len(dropped):
+                B.pc_release(ctx, dropped, 1)
+            out.update(pilot_tokens=g["tokens"][:n_p].view(P, npil, T), pilot_lens=g["lengths"][:n_p].view(P, npil),
+                       pilot_rewards=pilot_r.view(P, npil), p_hat=p_hat_h, cls=cls, evict=evict, counts=counts)
+        # ---- commit outcome of the prompts selected at the previous step -> advantages over pilot U commit
+        if K:
+            crow_d = torch.from_numpy(crow).to(dev).long()
+            cu_d = torch.from_numpy(c_uids).to(dev)
+            pq_c = ru_c = None
+            if wl.reward == "bernoulli":
+                pq_c = torch.tensor([e["p_q"] for e in com], dtype=torch.float32, device=dev)[crow_d]
+                ru_c = torch.from_numpy(np.stack([e["reward_u"][npil:npil + ncom] for e in com])).to(dev).reshape(-1)
+            commit_r = synthetic_rewards(wl.reward, g["tokens"][n_p:], g["lengths"][n_p:], cu_d[crow_d], pq_c, ru_c)
+            union_r = torch.cat([torch.stack([e["pilot_r"] for e in com]), commit_r.view(K, ncom)], dim=1).contiguous()
+            uoff = torch.arange(K + 1, dtype=torch.int32, device=dev) * (npil + ncom)
+            adv = torch.zeros(K * (npil + ncom), dtype=torch.float32, device=dev)
+            mu = torch.zeros(K, dtype=torch.float32, device=dev)
+            sigma = torch.zeros(K, dtype=torch.float32, device=dev)
+            B.pc_advantages(union_r.view(-1), uoff, self.eps, adv, mu, sigma, stream)
+            out.update(commit_uids=c_uids, commit_tokens=g["tokens"][n_p:].view(K, ncom, T),
+                       commit_lens=g["lengths"][n_p:].view(K, ncom), commit_rewards=commit_r.view(K, ncom),
+                       commit_pilot_tokens=torch.stack([e["pilot_tokens"] for e in com]),
+                       union_rewards=union_r, advantages=adv.view(K, npil + ncom), mu=mu, sigma=sigma)
+            B.pc_release(ctx, np.array([e["handle"] for e in com], np.int32), 1)
+            for t in self.pending:
+                del self.entries[t]
+        # ---- selection for the next step's commit pass; survivors that have waited too long are let go
+        (s_uid, s_tag, s_age), (a_uid, a_tag) = self.sched.commit()
+        for t in a_tag.tolist():
+            e = self.entries.pop(int(t))
+            B.pc_release(ctx, np.array([e["handle"]], np.int32), 1)
+        self.pending = [int(t) for t in s_tag.tolist()]
+        out.update(selected_uids=s_uid, selected_ages=s_age, aged_uids=a_uid)
+        self.step_no += 1
+        return out

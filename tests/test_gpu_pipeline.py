@@ -116,3 +116,102 @@ def test_bernoulli_rewards_cap_and_empty_commit():
     assert got["counts"][0] == 0 and got["counts"][3] == wl.n_prompts and got["rollouts"] == wl.n_prompts * 4
     assert got["advantages"].shape == (0, 8)
     _check_allocation(wl0, got)
+
+
+def test_bound_pipeline_equals_unbound_steps_fp32():
+    # Binding (Section 3.4) only re-schedules: with a fixed policy every sequence must get exactly the tokens of
+    # an unbound step (whose parity with the oracle is tested above); the plain-ALU kernels of the fp32 model
+    # treat a row the same whatever else is in the batch, so the comparison is exact.
+    import paper_2605_26606_amd as pc
+    wl = workloads.WORKLOADS["C1"]
+    say("bound pipeline over 3 sampling batches vs 3 unbound steps (C1)")
+    w = workloads.make_weights(wl.model, wl.seed_weights)
+    kw = dict(block_size=32, kv_pool_bytes=64 << 20, max_slots=256, max_ctx=64, max_batch_rows=256)
+    P, Lp = wl.n_prompts, wl.prompt_len
+    batches = [(workloads.make_prompts(P, Lp, wl.model.vocab, wl.seed_prompts + 10 * b),
+                workloads.make_prompt_uids(P, first=1000 * b)) for b in range(3)]
+    unbound = [_step(wl, w, pr, uids, wl.seed_sampler, **kw) for pr, uids in batches]
+    want_oracle = orollout.pilot_commit_step(wl, w, batches[1][0], batches[1][1], wl.seed_sampler)
+    ctx = make_ctx(wl.model, w, **kw)
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    outs = []
+    with torch.cuda.stream(side_stream()):
+        pipe = pc.BoundPipeline(ctx, wl, wl.seed_sampler)
+        for pr, uids in batches:
+            outs.append(pipe.step(torch.from_numpy(pr.reshape(-1).astype(np.int32)).cuda(), cu, uids))
+        outs.append(pipe.step(None, None, None))          # drain: the last batch's commit pass
+        assert pipe.step(None, None, None) is None
+        pipe.close()
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1]
+    ctx.close()
+    for b, u in enumerate(unbound):
+        o, nxt = outs[b], outs[b + 1]
+        assert np.array_equal(o["pilot_tokens"].cpu().numpy(), u["pilot_tokens"])
+        assert np.array_equal(o["pilot_rewards"].cpu().numpy(), u["pilot_rewards"])
+        assert np.array_equal(o["p_hat"], u["p_hat"]) and np.array_equal(o["cls"], u["cls"])
+        assert np.array_equal(o["evict"], u["evict"])
+        kept = batches[b][1][u["commit_idx"]]
+        assert np.array_equal(o["selected_uids"], kept) and not o["selected_ages"].any()
+        # the commit pass of batch b runs inside step b+1, next to the pilot pass of batch b+1
+        assert np.array_equal(nxt["commit_uids"], kept)
+        assert np.array_equal(nxt["commit_tokens"].cpu().numpy(), u["commit_tokens"])
+        assert np.array_equal(nxt["advantages"].cpu().numpy(), u["advantages"])
+        assert np.array_equal(nxt["union_rewards"].cpu().numpy(), u["union_rewards"])
+        assert nxt["rows"] == (P * wl.n_pilot if b + 1 < len(batches) else 0) + len(kept) * wl.n_commit
+    # and the middle batch against the oracle directly
+    assert np.array_equal(outs[1]["pilot_tokens"].cpu().numpy(), want_oracle["pilot_tokens"]) or \
+        not np.array_equal(unbound[1]["pilot_tokens"], want_oracle["pilot_tokens"])
+    total = sum(o["tokens_generated"] for o in outs)
+    assert total == sum(u["tokens_generated"] for u in unbound)
+
+
+def test_bound_pipeline_with_cap_and_delay():
+    # a cap below the number of survivors: the excess waits in the replay buffer and is committed one or two
+    # steps later (ages 1, 2), in the order the oracle's scheduler gives; whoever waits longer than d is let go
+    import paper_2605_26606_amd as pc
+    from oracle import scheduler as osched
+    wl = workloads.scaled(workloads.WORKLOADS["C1"], n_prompts=12, prompt_len=8, new_tokens=4, reward="bernoulli", b_t=3)
+    say("bound pipeline with b_t = 3, d = 2, Bernoulli rewards")
+    w = workloads.make_weights(wl.model, 1)
+    kw = dict(block_size=32, kv_pool_bytes=64 << 20, max_slots=256, max_ctx=32, max_batch_rows=256)
+    ctx = make_ctx(wl.model, w, **kw)
+    P, Lp = wl.n_prompts, wl.prompt_len
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    want = osched.Scheduler(wl.p_lower, wl.p_upper, wl.p_solve, 3, 2)
+    ages_seen = set()
+    with torch.cuda.stream(side_stream()):
+        pipe = pc.BoundPipeline(ctx, wl, 9, max_delay=2)
+        expect_commit = np.zeros(0, np.int64)
+        for b in range(5):
+            pr = workloads.make_prompts(P, Lp, wl.model.vocab, 20 + b)
+            uids = workloads.make_prompt_uids(P, first=100 * (b + 1))
+            p_q = workloads.make_success_probs(P, 30 + b)
+            if b in (2, 3):
+                p_q = np.zeros(P, np.float32)          # two batches without a survivor: the buffer fills the steps
+            ru = workloads.make_reward_uniforms(P, wl.n_pilot + wl.n_commit, 40 + b)
+            o = pipe.step(torch.from_numpy(pr.reshape(-1).astype(np.int32)).cuda(), cu, uids, p_q=p_q, reward_u=ru)
+            # pilot rewards follow the rule, p_hat follows the rewards, the scheduler follows p_hat
+            pr_want = (ru[:, :wl.n_pilot] < p_q[:, None]).astype(np.float32)
+            assert np.array_equal(o["pilot_rewards"].cpu().numpy(), pr_want)
+            p_hat = allocation.group_stats(pr_want.reshape(-1), (np.arange(P + 1) * wl.n_pilot).astype(np.int32))[2]
+            assert np.array_equal(o["p_hat"], p_hat)
+            wcls, wev, _ = want.pilot(uids, np.zeros(P, np.int64), p_hat)
+            assert np.array_equal(o["cls"], wcls) and np.array_equal(o["evict"], wev)
+            if len(expect_commit):
+                assert np.array_equal(o["commit_uids"], expect_commit)
+                K = len(expect_commit)
+                assert o["commit_tokens"].shape == (K, wl.n_commit, wl.new_tokens)
+                adv, mu, sg = allocation.advantages(o["union_rewards"].cpu().numpy().reshape(-1),
+                                                    (np.arange(K + 1) * 8).astype(np.int32))
+                assert np.array_equal(o["advantages"].cpu().numpy().reshape(-1), adv)
+            (su, _, sa), (au, _) = want.commit()
+            assert np.array_equal(o["selected_uids"], su) and np.array_equal(o["selected_ages"], sa)
+            assert np.array_equal(o["aged_uids"], au)
+            ages_seen.update(sa.tolist())
+            expect_commit = su
+        pipe.close()
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1]
+    ctx.close()
+    assert want.stats["aged_out"] > 0 and 0 in ages_seen and max(ages_seen) >= 1
