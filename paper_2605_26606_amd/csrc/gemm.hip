@@ -191,6 +191,21 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                                              (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
     };
 
+    auto issue_part = [&](int kt, int stage, int l) {     // load l of the tile (l < A_ITERS: operand A)
+        const int koff = min(kt, kt1 - 1) * BK;
+        T *sa = smem + stage * STAGE_ELEMS;
+        T *sw = sa + BM * BK;
+#pragma unroll
+        for (int i = 0; i < A_ITERS; ++i)
+            if (i == l)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + koff),
+                                                 (__attribute__((address_space(3))) void *)(sa + (NW * i + wave) * RPL * BK), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < W_ITERS; ++i)
+            if (A_ITERS + i == l)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pw[i] + koff),
+                                                 (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
+    };
     f32x16_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -219,14 +234,19 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
         for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const frag_t *)(sw + wrow[jj] * BK + (((2 * kk + fg) ^ wswz[jj]) * 8));
     };
-    auto compute = [&](int stage) {
+    auto compute = [&](int stage, int kt_next, int refill) {
         const T *sa = smem + stage * STAGE_ELEMS;
         const T *sw = sa + BM * BK;
         frag_t fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
         load_frags(sa, sw, 0, fa[0], fb[0]);
+        constexpr int KK = BK / 16;
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            if (kk + 1 < BK / 16) load_frags(sa, sw, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
+        for (int kk = 0; kk < KK; ++kk) {
+            // this step's share of the refill: the loads are spread over the tile's compute steps
+#pragma unroll
+            for (int l = 0; l < LOADS; ++l)
+                if (l * KK / LOADS == kk) issue_part(kt_next, refill, l);
+            if (kk + 1 < KK) load_frags(sa, sw, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -248,8 +268,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         const int refill = (stage == 0) ? NSTAGE - 1 : stage - 1;
-        issue_tile(kt + NSTAGE - 1, refill);
-        compute(stage);
+        compute(stage, kt + NSTAGE - 1, refill);
         stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
     }
     wait_vmcnt_le<0>();   // nothing may still be writing LDS when the block retires
@@ -334,10 +353,11 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> s
 };
 
 template <typename T> static void gemm_init_t() {
-    MfmaCfg<T, 256, 128, 4, 2, 3, 32>::init();
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
     MfmaCfg<T, 128, 128, 2, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
+    MfmaCfg<T, 128, 128, 2, 2, 2>::init();
+    MfmaCfg<T, 256, 64, 4, 2, 3>::init();
     MfmaCfg<T, 64, 64, 2, 2, 4>::init();
 }
 void gemm_init() {
@@ -369,10 +389,12 @@ template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
                               size_t slice_cap_floats, hipStream_t s) {
     // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
-    typedef MfmaCfg<T, 256, 128, 4, 2, 3, 32> CfgPrefill;   // 8 waves, 72 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
+    typedef CfgTall CfgPrefill;
     typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
+    typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 128, 64, 2, 2, 4> CfgMid;            // wave tile 64x32: long-K projections cut into K slices
+    typedef MfmaCfg<T, 256, 64, 4, 2, 3> CfgMidTall;        // the same for more than 256 rows
     typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;           // wave tile 32x32: many blocks for the small projections
     if (M > 512) {   // prefill: plenty of tiles
         CfgPrefill::run(A, W, C, M, N, K, epi, 1, s);
@@ -382,11 +404,21 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
     const int nb128 = (N + 127) / 128;
     if (epi == EPI_SWIGLU || nb128 >= 96) {   // wide outputs: no K slices needed
-        if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, s);   // a weight tile is fetched by exactly one block
+        if (M > 256 && M <= 384) CfgLarge2::run(A, W, C, M, N, K, epi, 1, s);   // three 128-row blocks, not two of 256
+        else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, s);   // a weight tile is fetched by exactly one block
         else CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
         return 1;
     }
     if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the feed-forward down projection)
+        if (M > 256) {
+            const int split = can_split ? CfgMidTall::pick_split(M, N, K, slice_cap_floats, 240) : 1;
+            if (split > 1) {
+                CfgMidTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+                return split;
+            }
+            CfgMidTall::run(A, W, C, M, N, K, epi, 1, s);
+            return 1;
+        }
         const int split = can_split ? CfgMid::pick_split(M, N, K, slice_cap_floats, 240) : 1;
         if (split > 1) {
             CfgMid::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
