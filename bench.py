@@ -94,6 +94,10 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--verbose", action="store_true", help="report each phase on stderr as it completes")
+    ap.add_argument("--b-t", type=int, default=0,
+                    help="cap on the prompts committed per step (Section 3.3 b_t); also bounds the KV pool, which "
+                         "otherwise is sized for every prompt being kept")
     ap.add_argument("--time-every", type=int, default=64)
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps eagerly (for counter runs: the profiler's counter mode and HIP graphs "
@@ -117,6 +121,8 @@ def main():
     wl = workloads.WORKLOADS[args.workload]
     if args.new_tokens:
         wl = workloads.scaled(wl, new_tokens=args.new_tokens)
+    if args.b_t:
+        wl = workloads.scaled(wl, b_t=args.b_t)
     m = wl.model
     torch.cuda.set_device(0)
     dev = "cuda:0"
@@ -126,7 +132,8 @@ def main():
     P, Lp, T = wl.n_prompts, wl.prompt_len, wl.new_tokens
     bound = args.binding_steps > 0
     # unbound: one pass at a time; bound: pilot and commit sequences decode together, two batches of prompts alive
-    n_max = P * (wl.n_pilot + wl.n_commit) if bound else P * max(wl.n_pilot, wl.n_commit)
+    P_commit = min(P, wl.b_t) if wl.b_t > 0 else P
+    n_max = P * wl.n_pilot + P_commit * wl.n_commit if bound else max(P * wl.n_pilot, P_commit * wl.n_commit)
     n_prompts_alive = 2 * P if bound else P
     kv_tokens = n_prompts_alive * Lp + n_max * (T + 64) + 4096
     ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
@@ -141,12 +148,19 @@ def main():
         if wl.reward == "bernoulli" else None
     stream = torch.cuda.Stream()
 
+    def say(msg):
+        if args.verbose:
+            sys.stderr.write("[bench %.0f s] %s\n" % (time.perf_counter() - t_start, msg))
+            sys.stderr.flush()
+
+    t_start = time.perf_counter()
+
     def one_step(seed, timed_steps=None, timings=None):
         with torch.cuda.stream(stream):
             return pc.pilot_commit_step(ctx, wl, toks, cu, uids, seed, eos_id, 0.0, p_q, ru,
                                         time_class=pc.PC_KERNEL_ATTN_DECODE if timed_steps is not None else -1,
                                         time_every=args.time_every if timed_steps is not None else 0,
-                                        timed_steps=timed_steps, timings=timings)
+                                        timed_steps=timed_steps, timings=timings, log=say)
 
     for i in range(args.warmup):
         one_step(wl.seed_sampler + 1000 + i)
@@ -175,7 +189,7 @@ def main():
         pilot_t = [t for (which, t, _, _) in timed_steps if which == "pilot"]
         traffic = counter_traffic_bytes(P * wl.n_pilot, Lp, sum(pilot_t) / max(1, len(pilot_t))) \
             if len(pilot_t) == len(timed_steps) else None
-        roof = {"kernel": "attention_decode_mfma_kernel<f16, direct, 4 waves> (pilot pass, 256 sequences)", "bound": "hbm", "achieved": round(achieved, 1),
+        roof = {"kernel": "attention_decode_mfma_kernel<f16, direct, 4 waves> (pilot pass, %d sequences)" % (P * wl.n_pilot), "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(avg_ms * 1e3, 2), "event_bracket_us": round(bracket_ms * 1e3, 2),
                 "launches_timed": int(attn_launches),

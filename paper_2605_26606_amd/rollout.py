@@ -139,11 +139,14 @@ def synthetic_rewards(rule: str, tokens: torch.Tensor, lengths: torch.Tensor, pr
 def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: np.ndarray, prompt_uids: np.ndarray,
                       seed: int, eos_id: int = -1, eos_logit_bias: float = 0.0, p_q: Optional[np.ndarray] = None,
                       reward_u: Optional[np.ndarray] = None, stream=None, eps: float = 1e-6, time_class: int = -1,
-                      time_every: int = 0, timed_steps: Optional[list] = None, timings: Optional[dict] = None):
+                      time_every: int = 0, timed_steps: Optional[list] = None, timings: Optional[dict] = None,
+                      log=None):
     """One pilot + commit step for the batch of prompts.  Returns a dict of
     device tensors / host counts mirroring the quantities of Algorithm 1.
     `timings` (optional dict) receives prefill_ms / pilot_ms / commit_ms from
-    events on the current stream."""
+    events on the current stream.  `log` (optional callable) is told when a
+    phase has been handed to the GPU and when the selection is known."""
+    log = log or (lambda msg: None)
     dev = prompt_tokens.device
     P = len(cu_lens) - 1
     V = ctx.vocab
@@ -161,6 +164,7 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     mark()
     handles = B.pc_prefill_shared(ctx, prompt_tokens, cu_lens, last_logits, stream)
     mark()
+    log("prefill of %d prompts enqueued" % P)
     uid_d = torch.from_numpy(uids).to(dev)
     pq_d = None if p_q is None else torch.from_numpy(np.asarray(p_q, np.float32)).to(dev)
     ru_d = None if reward_u is None else torch.from_numpy(np.asarray(reward_u, np.float32)).to(dev)
@@ -193,6 +197,7 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     counts_h = counts.cpu().numpy()            # the one read-back the method needs: the commit pass's size
     K = int(counts_h[0])
     kept = commit_idx[:K].cpu().numpy()
+    log("pilot pass done (%d sequences x %d tokens); %d of %d prompts kept" % (P * npil, T, K, P))
 
     # ---- commit pass: n_commit more rollouts for the kept prompts only; prefix KV is reused
     mark()
@@ -221,6 +226,7 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     if K:
         B.pc_advantages(union_r.view(-1), uoff, eps, adv, mu, sigma, stream)
     n_tok = int(g["lengths"].sum().item()) + (int(gc["lengths"].sum().item()) if K else 0)
+    log("commit pass done (%d sequences)" % (K * ncom))
     if timings is not None:
         torch.cuda.current_stream().synchronize()
         timings.update(prefill_ms=marks[0].elapsed_time(marks[1]), pilot_ms=marks[1].elapsed_time(marks[2]),
