@@ -26,7 +26,7 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
              seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
              eos_logit_bias: float = 0.0, stream=None, keep_logits_rows: Optional[np.ndarray] = None,
              poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None,
-             compact: bool = True):
+             compact: bool = True, keep_logprobs: bool = False):
     """Samples one completion per entry of `handles` (prompt handles, one per
     sequence).  Token 0 comes from the prompt's prefill logits
     (first_logits[logit_rows[i]]); tokens 1.. from decode steps.
@@ -35,6 +35,10 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
     when enough sequences have stopped (`compact`), they are released and the
     decode batch shrinks to the live ones (ragged stop), and the pass ends as
     soon as none is left.
+
+    keep_logprobs: also return logprobs [n, T] fp32, the log-probability of
+    every sampled token under the sampling distribution (the pi_theta_old of
+    Eq. 2; 0 after a sequence's end).
 
     Returns dict(tokens [n, T] int32 device (eos_id-padded after the end when
     EOS is on), lengths [n] int32 device, steps_run, rows_decoded (sum of the
@@ -62,9 +66,13 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
         keep_mask = torch.zeros(n, dtype=torch.bool, device=dev)
         keep_mask[keep] = True
     active = None                      # original index of each batch row; None = identity
-    B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, None,
+    lp_hist = torch.zeros((T, n), dtype=torch.float32, device=dev) if keep_logprobs else None
+    lp = torch.zeros(n, dtype=torch.float32, device=dev) if keep_logprobs else None
+    B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, lp,
                 finished, stream)
     hist[0, :n].copy_(cur)
+    if keep_logprobs:
+        lp_hist[0].copy_(lp)
     if keep is not None:
         out["logits"].append(first_logits[rows_d.long()[keep]].clone())
         out["logits_rows"].append(keep.clone())
@@ -84,6 +92,8 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
                 uid_d = uid_d[alive_d].contiguous()
                 finished = finished[alive_d].contiguous()
                 logits = logits[:len(alive)]
+                if keep_logprobs:
+                    lp = lp[:len(alive)]
         m = len(seqs)
         if time_every > 0 and t % time_every == time_every // 2:
             # this step runs eagerly with HIP events around every launch of one kernel class
@@ -100,12 +110,16 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
                 sel = keep_mask[active]
                 out["logits"].append(logits[sel].clone())
                 out["logits_rows"].append(active[sel].clone())
-        B.pc_sample(logits, None, m, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, None,
+        B.pc_sample(logits, None, m, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, lp,
                     finished, stream)
         if active is None:
             hist[t, :n].copy_(cur)
+            if keep_logprobs:
+                lp_hist[t].copy_(lp)
         else:
             hist[t].index_copy_(0, active, cur)
+            if keep_logprobs:
+                lp_hist[t].index_copy_(0, active, lp)
         steps += 1
     B.pc_release(ctx, seqs, 0)
     toks = hist[:, :n].t().contiguous()
@@ -117,6 +131,8 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
     else:
         lengths = torch.full((n,), T, dtype=torch.int32, device=dev)
     out.update(tokens=toks, lengths=lengths, steps_run=steps, rows_decoded=rows_decoded)
+    if keep_logprobs:
+        out["logprobs"] = lp_hist.t().contiguous()
     return out
 
 

@@ -79,7 +79,7 @@ def _run_generate(model, w_cpu, prompts_list, G, T, seed, ctx_kw, opts=(), tempe
         uids = (rows.astype(np.int64) * 65536 + np.tile(np.arange(G), P))
         n = P * G
         g = pc.generate(ctx, handles[rows], rows, last, uids, T, temperature, seed, eos_id, bias,
-                        keep_logits_rows=np.arange(n), poll_every=poll_every, compact=compact)
+                        keep_logits_rows=np.arange(n), poll_every=poll_every, compact=compact, keep_logprobs=True)
         pc.pc_release(ctx, handles, 1)
     torch.cuda.synchronize()
     free, total = pc.pc_kv_blocks(ctx)
@@ -90,6 +90,7 @@ def _run_generate(model, w_cpu, prompts_list, G, T, seed, ctx_kw, opts=(), tempe
         logits[t, lr.cpu().numpy()] = lg.cpu().numpy()
     out = dict(tokens=g["tokens"].cpu().numpy(), lengths=g["lengths"].cpu().numpy(), logits=logits,
                last=last.cpu().numpy(), uids=uids, rows=rows, steps_run=g["steps_run"],
+               logprobs=g["logprobs"].cpu().numpy(),
                rows_decoded=g["rows_decoded"])
     ctx.close()
     return out
@@ -104,6 +105,14 @@ def _check(model, w, prompts_list, out, seed, tol, seqs, temperature=1.0, eos_id
         gl = out["logits"][:L, i]
         err, s2, c, a_same, a_own = _teacher_forced(model, w, prompts_list[out["rows"][i]], gen, gl,
                                                     int(out["uids"][i]), seed, temperature, eos_id, bias)
+        # the log-probability handed on with every token (pi_theta_old of Eq. 2): log-softmax of the logits the
+        # token was sampled from, at the sampled token; exactly 0 after the end
+        for t in range(L):
+            u = philox.sampling_uniform(seed, int(out["uids"][i]), t)
+            tok, lp = sampler.sample_token(gl[t], temperature, u, eos_id, bias)
+            if tok == gen[t]:
+                assert abs(lp - out["logprobs"][i, t]) <= 1e-4 * max(1.0, abs(lp)), (i, t, lp, out["logprobs"][i, t])
+        assert not out["logprobs"][i, L:].any()
         worst = max(worst, err)
         sq += s2
         cnt += c
