@@ -134,18 +134,22 @@ void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *ga
 }
 
 // ------------------------------------------------------------------ RoPE + KV append
-// One block per row.  The pair (i, i + hd/2) of every q and k head turns by the
-// angle pos * theta^(-2i/hd) (cos/sin tables are built on the host in double).
+// The pair (i, i + hd/2) of every q and k head turns by the angle pos * theta^(-2i/hd) (cos/sin tables are
+// built on the host in double).  Grid (rows, item chunks): a row's work items are its q pairs, then its k
+// pairs, then its v elements; every thread takes exactly one, so all of a row's loads are in flight at once.
 template <typename T>
-__global__ void rope_append_kernel(const float *__restrict__ qkv, int S, int rows,
-                                   const int32_t *__restrict__ row_slot,
-                                   const int32_t *__restrict__ row_pos, const int32_t *__restrict__ slot_len,
-                                   const float *__restrict__ rope_cos, const float *__restrict__ rope_sin, int hq,
-                                   KvGeom kv, int layer, T *__restrict__ q_out) {
+__global__ __launch_bounds__(256) void rope_append_kernel(const float *__restrict__ qkv, int S, int rows,
+                                                          const int32_t *__restrict__ row_slot,
+                                                          const int32_t *__restrict__ row_pos,
+                                                          const int32_t *__restrict__ slot_len,
+                                                          const float *__restrict__ rope_cos,
+                                                          const float *__restrict__ rope_sin, int hq, KvGeom kv,
+                                                          int layer, T *__restrict__ q_out) {
     const int r = blockIdx.x;
     const int hd = kv.head_dim, half = hd / 2, hkv = kv.n_kv_heads, bs = kv.block_size;
-    const int slot = row_slot[r];
-    const int pos = row_pos ? row_pos[r] : slot_len[slot];
+    const int nq = hq * half, nk = hkv * half, nv = hkv * hd;
+    const int item = blockIdx.y * 256 + threadIdx.x;
+    if (item >= nq + nk + nv) return;
     const int width = (hq + 2 * hkv) * hd;
     const float *row = qkv + (int64_t)r * width;
     const int64_t zs = (int64_t)rows * width;   // distance between K slices
@@ -154,34 +158,31 @@ __global__ void rope_append_kernel(const float *__restrict__ qkv, int S, int row
         for (int z = 1; z < S; ++z) v += row[z * zs + c];
         return v;
     };
-    const float *cs = rope_cos + (int64_t)pos * half;
-    const float *sn = rope_sin + (int64_t)pos * half;
+    const int slot = row_slot[r];
+    const int pos = row_pos ? row_pos[r] : slot_len[slot];
+    if (item < nq) {
+        const int head = item / half, j = item % half;
+        const float x1 = val(head * hd + j), x2 = val(head * hd + j + half);
+        const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
+        T *qd = q_out + (int64_t)r * hq * hd + head * hd;
+        qd[j] = from_f32<T>(x1 * c - x2 * sgn);
+        qd[j + half] = from_f32<T>(x2 * c + x1 * sgn);
+        return;
+    }
     const int blk = kv.block_table[(int64_t)slot * kv.max_blocks_per_slot + pos / bs];
     const int tin = pos % bs;
     T *pool = (T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems();
-
-    // q heads
-    for (int i = threadIdx.x; i < hq * half; i += blockDim.x) {
-        int head = i / half, j = i % half;
-        float x1 = val(head * hd + j), x2 = val(head * hd + j + half);
-        float c = cs[j], sgn = sn[j];
-        q_out[(int64_t)r * hq * hd + head * hd + j] = from_f32<T>(x1 * c - x2 * sgn);
-        q_out[(int64_t)r * hq * hd + head * hd + j + half] = from_f32<T>(x2 * c + x1 * sgn);
-    }
-    // k heads -> K [tok][hd]
-    const int koff = hq * hd;
-    for (int i = threadIdx.x; i < hkv * half; i += blockDim.x) {
-        int head = i / half, j = i % half;
-        float x1 = val(koff + head * hd + j), x2 = val(koff + head * hd + j + half);
-        float c = cs[j], sgn = sn[j];
+    if (item < nq + nk) {   // k heads -> K [tok][hd]
+        const int i = item - nq, head = i / half, j = i % half;
+        const int koff = hq * hd;
+        const float x1 = val(koff + head * hd + j), x2 = val(koff + head * hd + j + half);
+        const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
         T *kd = pool + (int64_t)head * kv.head_elems() + (int64_t)tin * hd;
         kd[j] = from_f32<T>(x1 * c - x2 * sgn);
         kd[j + half] = from_f32<T>(x2 * c + x1 * sgn);
-    }
-    // v heads -> V^T [hd][tok]
-    const int voff = koff + hkv * hd;
-    for (int i = threadIdx.x; i < hkv * hd; i += blockDim.x) {
-        int head = i / hd, j = i % hd;
+    } else {                // v heads -> V^T [hd][tok]
+        const int i = item - nq - nk, head = i / hd, j = i % hd;
+        const int voff = (hq + hkv) * hd;
         T *vd = pool + (int64_t)head * kv.head_elems() + (int64_t)bs * hd;
         vd[(int64_t)j * bs + tin] = from_f32<T>(val(voff + head * hd + j));
     }
@@ -191,14 +192,16 @@ void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_s
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
                         KvGeom kv, int layer, void *q_out, hipStream_t s) {
     if (rows <= 0) return;
+    const int items = hq * (kv.head_dim / 2) + kv.n_kv_heads * (kv.head_dim / 2) + kv.n_kv_heads * kv.head_dim;
+    const dim3 grid(rows, (items + 255) / 256);
     if (dtype == KD_F32)
-        rope_append_kernel<float><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+        rope_append_kernel<float><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                        layer, (float *)q_out);
     else if (dtype == KD_BF16)
-        rope_append_kernel<bf16_t><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+        rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                         layer, (bf16_t *)q_out);
     else
-        rope_append_kernel<f16_t><<<rows, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
+        rope_append_kernel<f16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
                                                        layer, (f16_t *)q_out);
 }
 
