@@ -210,7 +210,9 @@ def main():
         "metric": "rollout tokens/s on 1 MI355X (1.5B shape, G=8); decode HBM GB/s % of peak",
         "value": round(tokens / dt, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(dt * 1e3 / max(1, args.steps), 2), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": m.dtype, "data": "synthetic",
+        "vs_baseline": None,
+        # matrix-core inputs: IEEE half copies of the bf16 weights and half activations / KV, fp32 accumulation
+        "dtype": "f16" if m.dtype == "bf16" else m.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d prompts x %d tokens, pilot %d + commit %d rollouts on kept prompts, %d new "
                                "tokens, L%d d%d %dq/%dkv hd%d ff%d V%d, random init" %
                                (wl.name, P, Lp, wl.n_pilot, wl.n_commit, T, m.n_layers, m.d_model, m.n_q_heads,
