@@ -95,6 +95,10 @@ def main():
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--verbose", action="store_true", help="report each phase on stderr as it completes")
+    ap.add_argument("--eos-bias", default="0",
+                    help="logit bias on the EOS id of the workloads that stop on EOS: a number, or 'ragged' for "
+                         "ln(V / (T/2)), i.e. a stop hazard of about 2/T per step (mean length near T/2); "
+                         "0 is the literal reading (one id in V almost never fires)")
     ap.add_argument("--b-t", type=int, default=0,
                     help="cap on the prompts committed per step (Section 3.3 b_t); also bounds the KV pool, which "
                          "otherwise is sized for every prompt being kept")
@@ -143,6 +147,9 @@ def main():
     cu = (np.arange(P + 1) * Lp).astype(np.int32)
     toks = torch.from_numpy(prompts.reshape(-1).astype(np.int32)).to(dev)
     eos_id = workloads.make_eos_id(m.vocab, wl.seed_eos) if wl.eos else -1
+    import math
+    eos_bias = (math.log(m.vocab / (wl.new_tokens / 2.0)) if args.eos_bias == "ragged" else float(args.eos_bias)) \
+        if wl.eos else 0.0
     p_q = workloads.make_success_probs(P, wl.seed_reward) if wl.reward == "bernoulli" else None
     ru = workloads.make_reward_uniforms(P, wl.n_pilot + wl.n_commit, wl.seed_reward) \
         if wl.reward == "bernoulli" else None
@@ -157,7 +164,7 @@ def main():
 
     def one_step(seed, timed_steps=None, timings=None):
         with torch.cuda.stream(stream):
-            return pc.pilot_commit_step(ctx, wl, toks, cu, uids, seed, eos_id, 0.0, p_q, ru,
+            return pc.pilot_commit_step(ctx, wl, toks, cu, uids, seed, eos_id, eos_bias, p_q, ru,
                                         time_class=pc.PC_KERNEL_ATTN_DECODE if timed_steps is not None else -1,
                                         time_every=args.time_every if timed_steps is not None else 0,
                                         timed_steps=timed_steps, timings=timings, log=say)
@@ -203,6 +210,9 @@ def main():
             if K:
                 dec_bytes += decode_bytes_per_step(m, K, Lp, K * wl.n_commit, t)
         dec_ms += tm.get("pilot_ms", 0.0) + tm.get("commit_ms", 0.0)
+    ragged = eos_id >= 0 and eos_bias != 0.0
+    if ragged:   # sequences leave the batch early: the full-length byte counts above do not describe this run
+        roof, dec_bytes = None, 0.0
     prefill_flops = 2.0 * m.body_params() * P * Lp + 2.0 * m.lm_head_params() * P \
         + 2.0 * m.n_layers * P * m.n_q_heads * m.head_dim * Lp * Lp
     prefill_ms = sum(tm.get("prefill_ms", 0.0) for tm in timings) / max(1, len(timings))
@@ -217,12 +227,13 @@ def main():
                                "tokens, L%d d%d %dq/%dkv hd%d ff%d V%d, random init" %
                                (wl.name, P, Lp, wl.n_pilot, wl.n_commit, T, m.n_layers, m.d_model, m.n_q_heads,
                                 m.n_kv_heads, m.head_dim, m.d_ff, m.vocab),
+                   "eos_logit_bias": round(eos_bias, 3),
                    "kept_prompts": [int(o["counts"][0]) for o in outs],
                    "rollouts": [int(o["rollouts"]) for o in outs]},
         "roofline": roof,
         "decode": {"ms": round(dec_ms, 1), "steps": sum(o["decode_steps"] for o in outs),
-                   "algorithmic_GBps": round(dec_bytes / max(dec_ms, 1e-9) / 1e6, 1),
-                   "frac_hbm": round(dec_bytes / max(dec_ms, 1e-9) / 1e6 / HBM_PEAK_GBPS, 4)},
+                   "algorithmic_GBps": None if ragged else round(dec_bytes / max(dec_ms, 1e-9) / 1e6, 1),
+                   "frac_hbm": None if ragged else round(dec_bytes / max(dec_ms, 1e-9) / 1e6 / HBM_PEAK_GBPS, 4)},
         "prefill": {"ms": round(prefill_ms, 2), "TFLOPs": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9, 1),
                     "frac_mfma": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
@@ -235,7 +246,7 @@ def main():
             batches.append((torch.from_numpy(pr.reshape(-1).astype(np.int32)).to(dev),
                             workloads.make_prompt_uids(P, first=10000 * (b + 1))))
         with torch.cuda.stream(stream):
-            pipe = pc.BoundPipeline(ctx, wl, wl.seed_sampler + 7, eos_id)
+            pipe = pc.BoundPipeline(ctx, wl, wl.seed_sampler + 7, eos_id, eos_bias)
             torch.cuda.synchronize()
             marks, info = [time.perf_counter()], []
             for tk, uid_b in batches + [(None, None)]:
