@@ -96,21 +96,30 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
         const int b = min(vocab, wave * seg), e = min(vocab, b + seg);
         float m = -INFINITY;
         double s = 0.0;
-        for (int base = b; base < e; base += STRIDE) {
-            float v[VEC];
-            bool ok[VEC];
-            load_scaled<VEC>(x, base + lane * VEC, e, inv_t, eos_id, eos_bias, v, ok);
-            float lm = -INFINITY;
+        // four strides are fetched before the first is folded in (the fold is a serial chain, and a load
+        // per link would leave the memory latency exposed at every step); the order of the arithmetic is
+        // that of the plain loop
+        constexpr int AHEAD = 4;
+        for (int base = b; base < e; base += AHEAD * STRIDE) {
+            float v[AHEAD][VEC];
+            bool ok[AHEAD][VEC];
 #pragma unroll
-            for (int c = 0; c < VEC; ++c)
-                if (ok[c]) lm = fmaxf(lm, v[c]);
-            if (lm > m) {
-                s *= (double)expf(m - lm);   // m = -inf -> 0
-                m = lm;
+            for (int u = 0; u < AHEAD; ++u)
+                load_scaled<VEC>(x, base + u * STRIDE + lane * VEC, e, inv_t, eos_id, eos_bias, v[u], ok[u]);
+#pragma unroll
+            for (int u = 0; u < AHEAD; ++u) {
+                float lm = -INFINITY;
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    if (ok[u][c]) lm = fmaxf(lm, v[u][c]);
+                if (lm > m) {
+                    s *= (double)expf(m - lm);   // m = -inf -> 0
+                    m = lm;
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c)
+                    if (ok[u][c]) s += (double)expf(v[u][c] - m);
             }
-#pragma unroll
-            for (int c = 0; c < VEC; ++c)
-                if (ok[c]) s += (double)expf(v[c] - m);
         }
         const float wm = wave_max_f32(m);
         const double ws = wave_sum_d(m == -INFINITY ? 0.0 : s * (double)expf(m - wm));
