@@ -252,6 +252,15 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
                 for (int jj = 0; jj < TN; ++jj)
                     acc[i][jj] = Mma<T>::m32(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj]);
+            // instruction order asked of the compiler: after each matrix instruction one or two LDS fragment
+            // reads and one global->LDS load, instead of all reads in a burst behind the last product
+            // (measured: +5 % on the prefill shapes, neutral on the decode shapes)
+#pragma unroll
+            for (int g = 0; g < TM * TN; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, (TM + TN + TM * TN - 1) / (TM * TN), 0);
+                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+            }
         }
     };
 
