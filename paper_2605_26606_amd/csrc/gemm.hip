@@ -366,6 +366,7 @@ template <typename T> static void gemm_init_t() {
     MfmaCfg<T, 128, 128, 2, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
     MfmaCfg<T, 128, 128, 2, 2, 2>::init();
+    MfmaCfg<T, 128, 128, 2, 2, 3, 32>::init();
     MfmaCfg<T, 256, 64, 4, 2, 3>::init();
     MfmaCfg<T, 64, 64, 2, 2, 4>::init();
 }
@@ -402,6 +403,7 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     typedef CfgTall CfgPrefill;
     typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
     typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
+    typedef MfmaCfg<T, 128, 128, 2, 2, 3, 32> CfgLarge3;    // BK 32, 48 KB of LDS: three blocks per CU
     typedef MfmaCfg<T, 128, 64, 2, 2, 4> CfgMid;            // wave tile 64x32: long-K projections cut into K slices
     typedef MfmaCfg<T, 256, 64, 4, 2, 3> CfgMidTall;        // the same for more than 256 rows
     typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;           // wave tile 32x32: many blocks for the small projections
@@ -413,7 +415,8 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
     const int nb128 = (N + 127) / 128;
     if (epi == EPI_SWIGLU || nb128 >= 96) {   // wide outputs: no K slices needed
-        if (M > 256 && M <= 384) CfgLarge2::run(A, W, C, M, N, K, epi, 1, s);   // three 128-row blocks, not two of 256
+        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, s);               // four 128-row blocks, three per CU at a time
+        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, s);          // three 128-row blocks, not two of 256
         else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, s);   // a weight tile is fetched by exactly one block
         else CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
         return 1;

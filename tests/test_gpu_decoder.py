@@ -183,6 +183,7 @@ def test_bf16_plain_alu_path():
     (BF8, [100, 31], 3, 10, 64, 0.02, "f16"),             # split-K in the large-tile GEMM
     (BF8, [100, 31], 3, 10, 64, 0.02, "bf16"),
     (BF8, [12] * 75, 4, 5, 64, 0.02, "f16"),              # 300 decode rows: 128-row GEMM blocks in threes, tall K slices
+    (BF8, [12] * 105, 4, 4, 64, 0.02, "f16"),             # 420 decode rows: four 128-row blocks, BK 32
 ])
 def test_bf16_matrix_core_path(model, lens, G, T, bs, std, act):
     say("bf16 model, matrix-core path, %s activations, lens=%s G=%d T=%d std=%g" % (act, lens[:6], G, T, std))
