@@ -13,6 +13,10 @@ Modules
   allocation  group statistics (Eq. 3), pilot filter / eviction / commit set
               (Section 3.3, Algorithm 1), group-relative advantages, sampling
               cost (Section 4.3)
+  scheduler   multi-step scheduling: replay buffer, maximum delay, eviction (Algorithm 1,
+              Section 3.4)
+  scoring     log-probability of a given completion under the policy (Section 3.1,
+              the per-token factors of Eq. 2's ratio)
   rewards     the synthetic binary reward rules of the workloads
   rollout     pilot pass -> select -> commit pass -> advantages, end to end
 
