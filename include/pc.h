@@ -168,6 +168,23 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
  * Shared blocks are freed when their last user goes. */
 pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind);
 
+/* Teacher-forced scoring: log pi_theta(o_t | q, o_<t) for every completion
+ * token of S given sequences (Section 3.1: a rollout's probability is the
+ * product of these; Eq. 2's importance ratio is a ratio of them under two
+ * policies), at the given temperature.
+ *   tokens      device int32: the sequences (prompt, then completion), packed
+ *   cu_lens     host int32 [S+1]: sequence i is tokens[cu_lens[i] .. cu_lens[i+1])
+ *   prompt_len  host int32 [S]: the first prompt_len[i] >= 1 tokens of sequence
+ *               i are its prompt; its completion is the rest
+ *   logprob_out device fp32, packed in sequence order: len_i - prompt_len[i]
+ *               values for sequence i
+ * Same limits as pc_prefill_shared (a sequence fits max_ctx and
+ * max_batch_rows).  Uses KV blocks and slots while it runs and gives them
+ * back; the first call allocates a logits buffer (and synchronises once).
+ * PC_ERR_OOM if blocks or slots run out: nothing is kept. */
+pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, const int32_t *prompt_len,
+                   int32_t S, float temperature, float *logprob_out, void *stream);
+
 /* Samples one token per row: o_t ~ softmax(logits / temperature)
  * (Section 3.1 sampling; Section 4.2: temperature 1.0, top_p 1.0), by inverse
  * CDF with a Philox4x32-10 uniform keyed by (seed; step, sequence uid).

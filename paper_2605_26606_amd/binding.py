@@ -80,6 +80,7 @@ def library() -> C.CDLL:
             "pc_fork": [vp, vp, i32, i32, vp, vp],
             "pc_decode_step": [vp, vp, vp, i32, vp, vp],
             "pc_release": [vp, vp, i32, i32],
+            "pc_score": [vp, vp, vp, vp, i32, f32, vp, vp],
             "pc_sample": [vp, vp, i32, i32, f32, u64, vp, vp, i32, i32, f32, vp, vp, vp, vp],
             "pc_group_stats": [vp, vp, i32, vp, vp, vp, vp, vp],
             "pc_select_commit": [vp, i32, f32, f32, f32, i32, vp, vp, vp, vp, vp, vp],
@@ -233,6 +234,23 @@ def pc_decode_step(ctx: Context, seq, tokens_in: torch.Tensor, logits: torch.Ten
         raise ValueError("tokens_in / logits too small for %d sequences" % n)
     _check(library().pc_decode_step(ctx.handle, s.ctypes.data, _dev(tokens_in, torch.int32, "tokens_in"), n,
                                     _dev(logits, torch.float32, "logits"), _stream_ptr(stream)))
+
+
+def pc_score(ctx: Context, tokens: torch.Tensor, cu_lens, prompt_len, temperature: float, logprob_out: torch.Tensor,
+             stream=None):
+    """log pi(o_t | q, o_<t) of every completion token of the packed sequences (device int32 `tokens`,
+    host `cu_lens` [S+1] and `prompt_len` [S]) into `logprob_out` (device fp32, packed)."""
+    cu = _host_i32(cu_lens, "cu_lens")
+    pl = _host_i32(prompt_len, "prompt_len")
+    S = len(cu) - 1
+    if len(pl) != S:
+        raise ValueError("prompt_len must have one entry per sequence")
+    n_out = int((np.diff(cu) - pl).sum()) if S > 0 else 0
+    if S > 0 and (tokens.numel() < cu[-1] or logprob_out.numel() < n_out):
+        raise ValueError("tokens or logprob_out is too small")
+    _check(library().pc_score(ctx.handle, _dev(tokens, torch.int32, "tokens"), cu.ctypes.data, pl.ctypes.data, S,
+                              float(temperature), _dev(logprob_out, torch.float32, "logprob_out"),
+                              _stream_ptr(stream)))
 
 
 def pc_release(ctx: Context, ids, kind: int):

@@ -57,6 +57,8 @@ struct pc_ctx {
     float *rope_cos = nullptr, *rope_sin = nullptr;
     // activations
     float *h = nullptr, *qkv = nullptr, *attn_scratch = nullptr;
+    float *score_logits = nullptr;    // pc_score: logits of score_rows rows at a time (allocated on first use)
+    int score_rows = 0;
     void *a = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
     int32_t *d_meta = nullptr;   // row_slot | row_pos | cu_rows | prompt_slot | last_rows | copy pairs
     int32_t *d_dec_slot = nullptr;
@@ -120,7 +122,7 @@ void free_all(pc_ctx *ctx) {
     for (auto p : ctx->attn_norm) fr(p);
     for (auto p : ctx->ffn_norm) fr(p);
     fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
-    fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
+    fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->score_logits); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
     fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices); fr(ctx->lm_head_copy);
 }
 
@@ -476,28 +478,35 @@ pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_b
     return PC_OK;
 }
 
-pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
-                            int32_t *handle_out, float *last_logits, void *stream) {
-    if (!ctx || !cu_lens || !handle_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
-    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: negative prompt count");
-    if (P == 0) return PC_OK;
-    if (!prompt_tokens || !last_logits) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
-    hipStream_t st = (hipStream_t)stream;
+// What a scoring pass wants from the forward of the given sequences instead of the last rows' logits.
+struct ScoreRequest {
+    const int32_t *prompt_len;   // host [P]
+    float temperature;
+    float *out;                  // device, packed
+};
+
+// The forward of P packed sequences from position 0 (shared by pc_prefill_shared and pc_score): allocates a
+// prompt slot and KV blocks per sequence, runs the layers in chunks of whole sequences, and then either
+// writes the last row's logits of every sequence (last_logits) or the log-probabilities of the completion
+// tokens (score).
+static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
+                                   int32_t *handle_out, float *last_logits, const ScoreRequest *score,
+                                   hipStream_t st) {
     const pc_model_config &m = ctx->m;
     const int bs = ctx->c.block_size;
-    if (cu_lens[0] != 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: cu_lens[0] must be 0");
+    if (cu_lens[0] != 0) PC_FAIL(PC_ERR_INVALID_ARG, "forward: cu_lens[0] must be 0");
     int64_t need_blocks = 0;
     for (int p = 0; p < P; ++p) {
         const int len = cu_lens[p + 1] - cu_lens[p];
-        if (len <= 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d is empty", p);
-        if (len > ctx->c.max_ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d longer than max_ctx", p);
+        if (len <= 0) PC_FAIL(PC_ERR_INVALID_ARG, "forward: prompt %d is empty", p);
+        if (len > ctx->c.max_ctx) PC_FAIL(PC_ERR_INVALID_ARG, "forward: prompt %d longer than max_ctx", p);
         if (len > ctx->c.max_batch_rows)
-            PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: prompt %d longer than max_batch_rows", p);
+            PC_FAIL(PC_ERR_INVALID_ARG, "forward: prompt %d longer than max_batch_rows", p);
         need_blocks += (len + bs - 1) / bs;
     }
-    if ((size_t)P > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "pc_prefill_shared: out of slots");
+    if ((size_t)P > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "forward: out of slots");
     if ((size_t)need_blocks > ctx->free_blocks.size())
-        PC_FAIL(PC_ERR_OOM, "pc_prefill_shared: needs %lld KV blocks, %zu free", (long long)need_blocks,
+        PC_FAIL(PC_ERR_OOM, "forward: needs %lld KV blocks, %zu free", (long long)need_blocks,
                 ctx->free_blocks.size());
     // ---- allocate
     int smin = ctx->c.max_slots, smax = -1;
@@ -529,6 +538,7 @@ pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int
     int32_t *d_row_slot = ctx->d_meta, *d_row_pos = ctx->d_meta + R, *d_cu = ctx->d_meta + 2 * R,
             *d_pslot = d_cu + S + 1, *d_last = d_pslot + S;
     std::vector<int32_t> row_slot, row_pos, cu, pslot, last;
+    size_t score_done = 0;   // completion tokens scored so far (offset into the packed output)
     int p0 = 0;
     while (p0 < P) {
         int p1 = p0, rows = 0, max_len = 0;
@@ -560,15 +570,83 @@ pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int
         if (pending > 1)   // small chunk whose last projection was split: fold the slices into h first
             launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->slices,
                            pending, st);
-        launch_rmsnorm(ctx->kd, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
-        launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
-                    m.d_model, EPI_STORE_F32, nullptr, 0, st);
+        if (!score) {
+            launch_rmsnorm(ctx->kd, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
+            launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
+                        m.d_model, EPI_STORE_F32, nullptr, 0, st);
+        } else {
+            // rows whose NEXT token belongs to a completion: positions prompt_len-1 .. len-2 of every sequence
+            std::vector<int32_t> local, global;
+            for (int p = p0; p < p1; ++p) {
+                const int len = cu_lens[p + 1] - cu_lens[p];
+                for (int i = score->prompt_len[p] - 1; i + 1 < len; ++i) {
+                    local.push_back(cu[p - p0] + i);
+                    global.push_back(cu_lens[p] + i);
+                }
+            }
+            const int n_sc = (int)local.size();
+            if (n_sc > 0) {
+                // the row metadata is free again once the layers are enqueued (stream order)
+                PC_HIP(hipMemcpyAsync(d_row_slot, local.data(), (size_t)n_sc * 4, hipMemcpyHostToDevice, st));
+                PC_HIP(hipMemcpyAsync(d_row_pos, global.data(), (size_t)n_sc * 4, hipMemcpyHostToDevice, st));
+                for (int off = 0; off < n_sc; off += ctx->score_rows) {
+                    const int sr = std::min(ctx->score_rows, n_sc - off);
+                    launch_rmsnorm(ctx->kd, ctx->h, d_row_slot + off, ctx->final_norm, sr, m.d_model, m.rms_eps, ctx->a,
+                                   nullptr, 1, st);
+                    launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, ctx->score_logits, sr, m.vocab, m.d_model,
+                                EPI_STORE_F32, nullptr, 0, st);
+                    launch_logprob(ctx->score_logits, sr, m.vocab, score->temperature, prompt_tokens, d_row_pos + off,
+                                   score->out + score_done + off, st);
+                }
+                score_done += n_sc;
+            }
+        }
         rc = check_launch();
         if (rc != PC_OK) return rc;
         // the metadata buffers are reused by the next chunk: pageable copies above were staged at call time
         p0 = p1;
     }
     return PC_OK;
+}
+
+pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
+                            int32_t *handle_out, float *last_logits, void *stream) {
+    if (!ctx || !cu_lens || !handle_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: negative prompt count");
+    if (P == 0) return PC_OK;
+    if (!prompt_tokens || !last_logits) PC_FAIL(PC_ERR_INVALID_ARG, "pc_prefill_shared: null argument");
+    return forward_sequences(ctx, prompt_tokens, cu_lens, P, handle_out, last_logits, nullptr, (hipStream_t)stream);
+}
+
+pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, const int32_t *prompt_len, int32_t S,
+                   float temperature, float *logprob_out, void *stream) {
+    if (!ctx || !cu_lens || !prompt_len) PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: null argument");
+    if (S < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: negative sequence count");
+    if (S == 0) return PC_OK;
+    if (!tokens || !logprob_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: null argument");
+    if (!(temperature > 0.f)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: temperature must be positive");
+    if (cu_lens[0] != 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: cu_lens[0] must be 0");
+    for (int i = 0; i < S; ++i) {
+        const int len = cu_lens[i + 1] - cu_lens[i];
+        if (prompt_len[i] < 1 || prompt_len[i] > len)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_score: prompt_len[%d] = %d outside 1 .. %d", i, prompt_len[i], len);
+    }
+    if (!ctx->score_logits) {   // first use: room for the logits of up to 1024 rows at a time
+        const int rows = std::min(ctx->c.max_batch_rows, 1024);
+        pc_status rc = dev_alloc(&ctx->score_logits, (size_t)rows * ctx->m.vocab);
+        if (rc != PC_OK) return rc;
+        ctx->score_rows = rows;
+    }
+    std::vector<int32_t> handles((size_t)S, -1);
+    ScoreRequest req{prompt_len, temperature, logprob_out};
+    const pc_status rc = forward_sequences(ctx, tokens, cu_lens, S, handles.data(), nullptr, &req, (hipStream_t)stream);
+    // the sequences were only passing through: their slots and blocks go back (work already enqueued keeps its
+    // place in the stream ahead of whoever reuses them)
+    for (int32_t h : handles)
+        if (h >= 0 && ctx->slots[h].used) release_slot(ctx, h);
+    ctx->dec_seq.clear();
+    ctx->list_version++;
+    return rc;
 }
 
 pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens, int32_t *seq_out,

@@ -178,6 +178,9 @@ void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t s);
 void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, uint64_t seed,
                    const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
                    int32_t *tokens_out, float *logprob_out, uint8_t *finished, hipStream_t s);
+// out[r] = log softmax(logits[r] / T)[tokens[token_index[r] + 1]]
+void launch_logprob(const float *logits, int n, int vocab, float temperature, const int32_t *tokens,
+                    const int32_t *token_index, float *out, hipStream_t s);
 void launch_group_stats(const float *rewards, const int32_t *off, int P, int32_t *n_pos, int32_t *n_tot, float *mean,
                         float *var, hipStream_t s);
 void launch_select_commit(const float *p_hat, int P, float lo, float hi, float solve, int b_t, uint8_t *cls,

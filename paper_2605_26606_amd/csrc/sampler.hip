@@ -280,4 +280,66 @@ void launch_sample(const float *logits, const int32_t *logit_row, int n, int voc
                                                            finished);
 }
 
+// log softmax(logits / T) at a given token per row (teacher-forced scoring: Section 3.1, the per-token
+// factors of Eq. 2's ratio).  One block of 16 waves per row, the row is read once: online (max, sum) per
+// thread, combined over the block; sums in double.  The target of row r is tokens[token_index[r] + 1]:
+// the token that follows the position whose logits the row holds.
+template <int VEC>
+__global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void logprob_kernel(const float *__restrict__ logits, int vocab,
+                                                                      float inv_t,
+                                                                      const int32_t *__restrict__ tokens,
+                                                                      const int32_t *__restrict__ token_index,
+                                                                      float *__restrict__ out) {
+    __shared__ float s_wm[SAMPLE_WAVES];
+    __shared__ double s_ws[SAMPLE_WAVES];
+    const int row = blockIdx.x, tid = threadIdx.x, lane = tid % WAVE, wave = tid / WAVE;
+    const float *x = logits + (int64_t)row * vocab;
+    float m = -INFINITY;
+    double s = 0.0;
+    for (int base = tid * VEC; base < vocab; base += SAMPLE_WAVES * WAVE * VEC) {
+        float v[VEC];
+        bool ok[VEC];
+        load_scaled<VEC>(x, base, vocab, inv_t, -1, 0.f, v, ok);
+        float lm = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+            if (ok[c]) lm = fmaxf(lm, v[c]);
+        if (lm > m) {
+            s *= (double)expf(m - lm);
+            m = lm;
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+            if (ok[c]) s += (double)expf(v[c] - m);
+    }
+    const float wm = wave_max_f32(m);
+    const double ws = wave_sum_d(m == -INFINITY ? 0.0 : s * (double)expf(m - wm));
+    if (lane == 0) {
+        s_wm[wave] = wm;
+        s_ws[wave] = ws;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        float M = -INFINITY;
+        for (int w = 0; w < SAMPLE_WAVES; ++w) M = fmaxf(M, s_wm[w]);
+        double Z = 0.0;
+        for (int w = 0; w < SAMPLE_WAVES; ++w) Z += (s_wm[w] == -INFINITY) ? 0.0 : s_ws[w] * (double)expf(s_wm[w] - M);
+        const int target = tokens[token_index[row] + 1];
+        float lp = -INFINITY;
+        if (target >= 0 && target < vocab) lp = (float)((double)(x[target] * inv_t) - (double)M - log(Z));
+        out[row] = lp;
+    }
+}
+
+void launch_logprob(const float *logits, int n, int vocab, float temperature, const int32_t *tokens,
+                    const int32_t *token_index, float *out, hipStream_t s) {
+    if (n <= 0) return;
+    const float inv_t = 1.0f / temperature;
+    const bool vec = (vocab % 4 == 0) && (((uintptr_t)logits) % 16 == 0);
+    if (vec)
+        logprob_kernel<4><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, vocab, inv_t, tokens, token_index, out);
+    else
+        logprob_kernel<1><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, vocab, inv_t, tokens, token_index, out);
+}
+
 }  // namespace pc
