@@ -109,6 +109,8 @@ def main():
     ap.add_argument("--binding-steps", type=int, default=4,
                     help="after the timed steps, also run this many sampling batches through the bound pipeline "
                          "(commit pass of step t-1 in one decode batch with the pilot pass of step t); 0 = skip")
+    ap.add_argument("--no-score", action="store_true",
+                    help="skip the scoring leg (pc_score over the last step's pilot rollouts)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size reference of the counter runs)")
     args = ap.parse_args()
@@ -265,6 +267,34 @@ def main():
             "steady_tokens_per_s": round(sum(i[1] for i in mid) / sum(i[2] for i in mid), 1),
             "rows_per_pass": [i[0] for i in info], "ms_per_pass": [round(i[2] * 1e3, 1) for i in info],
             "note": "ramp-up (pilot only) and drain (commit only) passes included in value, excluded from steady"}
+    if not args.no_score and outs:
+        # teacher-forced scoring of the pilot rollouts just generated (the per-token factors of Eq. 2's ratio):
+        # one forward over prompt + completion of every rollout, log-softmax at the next token
+        o = outs[-1]
+        npil = wl.n_pilot
+        comp = o["pilot_tokens"].reshape(P * npil, T)
+        lens = o["pilot_lens"].reshape(-1).cpu().numpy()
+        pr_d = toks.view(P, Lp).repeat_interleave(npil, dim=0)
+        seqs = torch.cat([pr_d, comp], dim=1)
+        keep = torch.arange(Lp + T, device=dev)[None, :] < (Lp + torch.from_numpy(lens).to(dev))[:, None]
+        packed = seqs[keep].contiguous()
+        cu_s = np.concatenate([[0], np.cumsum(Lp + lens)]).astype(np.int32)
+        n_sc = int(lens.sum())
+        lp_out = torch.empty(n_sc, dtype=torch.float32, device=dev)
+        with torch.cuda.stream(stream):
+            pc.pc_score(ctx, packed, cu_s, np.full(P * npil, Lp, np.int32), wl.temperature, lp_out)   # allocates once
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            pc.pc_score(ctx, packed, cu_s, np.full(P * npil, Lp, np.int32), wl.temperature, lp_out)
+            torch.cuda.synchronize()
+            dt_s = time.perf_counter() - t1
+        rows_s = int(cu_s[-1])
+        flops = 2.0 * m.body_params() * rows_s + 2.0 * m.lm_head_params() * n_sc \
+            + sum(2.0 * m.n_layers * m.n_q_heads * m.head_dim * float(l) * float(l) for l in (Lp + lens))
+        result["scoring"] = {"value": round(n_sc / dt_s, 1), "unit": "scored tokens/s", "sequences": P * npil,
+                             "rows": rows_s, "ms": round(dt_s * 1e3, 1), "TFLOPs": round(flops / dt_s / 1e12, 1),
+                             "frac_mfma": round(flops / dt_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
+                             "mean_logprob": round(float(lp_out.mean().item()), 4)}
     if args.calibrate_copy:   # rocprofv3 --pmc runs scale FETCH_SIZE / WRITE_SIZE by what this copy reads
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
