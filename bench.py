@@ -142,6 +142,8 @@ def main():
     n_max = P * wl.n_pilot + P_commit * wl.n_commit if bound else max(P * wl.n_pilot, P_commit * wl.n_commit)
     n_prompts_alive = 2 * P if bound else P
     kv_tokens = n_prompts_alive * Lp + n_max * (T + 64) + 4096
+    if not args.no_score:   # the scoring leg runs every pilot rollout (prompt + completion) through the forward
+        kv_tokens = max(kv_tokens, P * wl.n_pilot * (Lp + T + 64) + 4096)
     ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
                      max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
     if args.no_graph:

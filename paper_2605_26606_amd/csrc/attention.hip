@@ -213,13 +213,24 @@ __device__ inline void state_init(AttnState &st) {
 }
 
 // ---------------------------------------------------------------- prefill
-// grid (query tiles of 16, q heads, prompts), one wave per block
+// One wave per block: 16 query positions of one head of one prompt.  1-D grid laid out die by die (workgroup i
+// runs on die i % 8): all blocks of a (prompt, kv head) pair -- its query heads times its query tiles -- run back
+// to back on ONE die, so that pair's K/V is fetched from HBM once and then served from that die's L2 (the
+// K/V of a whole chunk does not fit an L2, and in plain order every die would stream all of it).
 template <typename T>
 __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__restrict__ q,
                                                                     const int32_t *__restrict__ cu_rows,
                                                                     const int32_t *__restrict__ prompt_slot, int hq,
-                                                                    KvGeom kv, int layer, T *__restrict__ out) {
-    const int p = blockIdx.z, head = blockIdx.y, q0 = blockIdx.x * 16;
+                                                                    KvGeom kv, int layer, int n_prompts, int n_qt,
+                                                                    T *__restrict__ out) {
+    const int rep_h = hq / kv.n_kv_heads, items = rep_h * n_qt;
+    const int b = blockIdx.x, die = b % 8, j = b / 8;
+    const int unit = (j / items) * 8 + die;                      // (prompt, kv head)
+    if (unit >= n_prompts * kv.n_kv_heads) return;
+    const int item = j % items;
+    const int p = unit / kv.n_kv_heads;
+    const int head = (unit % kv.n_kv_heads) * rep_h + item / n_qt;
+    const int q0 = (n_qt - 1 - item % n_qt) * 16;                // long causal ranges first
     const int row0 = cu_rows[p], len = cu_rows[p + 1] - row0;
     if (q0 >= len) return;
     const int lane = threadIdx.x, i = lane % 16, g = lane / 16;
@@ -260,13 +271,15 @@ __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__r
 void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
                                    int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
     if (n_prompts <= 0 || max_len <= 0) return;
-    dim3 grid((max_len + 15) / 16, hq, n_prompts);
+    const int n_qt = (max_len + 15) / 16, items = (hq / kv.n_kv_heads) * n_qt;
+    const int units = n_prompts * kv.n_kv_heads;
+    const unsigned grid = (unsigned)((units + 7) / 8 * 8) * (unsigned)items;
     if (dtype == KD_BF16)
         attention_prefill_mfma_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
-                                                                  (bf16_t *)out);
+                                                                  n_prompts, n_qt, (bf16_t *)out);
     else
         attention_prefill_mfma_kernel<f16_t><<<grid, 64, 0, s>>>((const f16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
-                                                                 (f16_t *)out);
+                                                                 n_prompts, n_qt, (f16_t *)out);
 }
 
 // ---------------------------------------------------------------- decode
