@@ -137,12 +137,14 @@ template <typename T> __device__ inline typename Mma<T>::frag zero_frag() {
     return __builtin_bit_cast(typename Mma<T>::frag, (u32x4){0, 0, 0, 0});
 }
 
-// Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end.
+// Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end, for NH query-head groups
+// that share the kv head: the K and V fragments of a tile are loaded once and used for every group.
 // Tokens > col_limit (this lane's column) or >= tok_end are masked.
-template <typename T>
+template <typename T, int NH>
 __device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t block_elems,
-                                    const int32_t *__restrict__ table, int bs, const typename Mma<T>::frag (&qf)[4], int tile_begin,
-                                    int tile_step, int tok_end, int col_limit, float scale_log2, AttnState &st) {
+                                    const int32_t *__restrict__ table, int bs,
+                                    const typename Mma<T>::frag (&qf)[NH][4], int tile_begin, int tile_step, int tok_end,
+                                    int col_limit, float scale_log2, AttnState (&st)[NH]) {
     const int lane = threadIdx.x % WAVE, i = lane % 16, g = lane / 16;
     const int krow = 8 * (i / 4) + (i % 4);   // tile u reads token krow + 4u: lane (column, g) then owns tokens 8g..8g+7
     for (int t0 = tile_begin; t0 < tok_end; t0 += tile_step) {
@@ -156,16 +158,6 @@ __device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t blo
             for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld_frag(kb + (int64_t)(tin + krow + 4 * u) * HD + 32 * kk + 8 * g);
 #pragma unroll
         for (int nn = 0; nn < 8; ++nn) vf[nn] = ld_frag(vb + (int64_t)(16 * nn + i) * bs + tin + 8 * g);
-
-        f32x4 s[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) s[u] = Mma<T>::m16(ka[u][kk], qf[kk], s[u]);
-        }
-        // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
-        float mx = -INFINITY;
         bool ok[2][4];
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -173,34 +165,50 @@ __device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t blo
             for (int v = 0; v < 4; ++v) {
                 const int tok = t0 + 8 * g + 4 * u + v;
                 ok[u][v] = (tok <= col_limit) && (tok < tok_end);
-                if (ok[u][v]) mx = fmaxf(mx, s[u][v]);
             }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-        const float m_new = fmaxf(st.m, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float corr = exp2f((st.m - m_use) * scale_log2);   // st.m = -inf -> 0
-        float p[2][4], psum = 0.f;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int h = 0; h < NH; ++h) {
+            f32x4 s[2];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                p[u][v] = ok[u][v] ? exp2f((s[u][v] - m_use) * scale_log2) : 0.f;
-                psum += p[u][v];
+            for (int u = 0; u < 2; ++u) {
+                s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) s[u] = Mma<T>::m16(ka[u][kk], qf[h][kk], s[u]);
             }
-        st.l = st.l * corr + psum;
-        st.m = m_new;
-        float c4[4];
+            // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
+            float mx = -INFINITY;
 #pragma unroll
-        for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
-        u32x4 pw = {pack2<T>(p[0][0], p[0][1]), pack2<T>(p[0][2], p[0][3]), pack2<T>(p[1][0], p[1][1]),
-                    pack2<T>(p[1][2], p[1][3])};
-        const typename Mma<T>::frag pa = __builtin_bit_cast(typename Mma<T>::frag, pw);
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int nn = 0; nn < 8; ++nn) {
+                for (int v = 0; v < 4; ++v)
+                    if (ok[u][v]) mx = fmaxf(mx, s[u][v]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+            const float m_new = fmaxf(st[h].m, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float corr = exp2f((st[h].m - m_use) * scale_log2);   // st.m = -inf -> 0
+            float p[2][4], psum = 0.f;
 #pragma unroll
-            for (int v = 0; v < 4; ++v) st.o[nn][v] *= c4[v];
-            st.o[nn] = Mma<T>::m16(pa, vf[nn], st.o[nn]);
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    p[u][v] = ok[u][v] ? exp2f((s[u][v] - m_use) * scale_log2) : 0.f;
+                    psum += p[u][v];
+                }
+            st[h].l = st[h].l * corr + psum;
+            st[h].m = m_new;
+            float c4[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
+            u32x4 pw = {pack2<T>(p[0][0], p[0][1]), pack2<T>(p[0][2], p[0][3]), pack2<T>(p[1][0], p[1][1]),
+                        pack2<T>(p[1][2], p[1][3])};
+            const typename Mma<T>::frag pa = __builtin_bit_cast(typename Mma<T>::frag, pw);
+#pragma unroll
+            for (int nn = 0; nn < 8; ++nn) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) st[h].o[nn][v] *= c4[v];
+                st[h].o[nn] = Mma<T>::m16(pa, vf[nn], st[h].o[nn]);
+            }
         }
     }
 }
@@ -213,73 +221,92 @@ __device__ inline void state_init(AttnState &st) {
 }
 
 // ---------------------------------------------------------------- prefill
-// One wave per block: 16 query positions of one head of one prompt.  1-D grid laid out die by die (workgroup i
-// runs on die i % 8): all blocks of a (prompt, kv head) pair -- its query heads times its query tiles -- run back
-// to back on ONE die, so that pair's K/V is fetched from HBM once and then served from that die's L2 (the
-// K/V of a whole chunk does not fit an L2, and in plain order every die would stream all of it).
-template <typename T>
+// One wave per block: 16 query positions of NH query heads (that share a kv head) of one prompt; the K/V
+// fragments of a tile are loaded once for the NH heads.  1-D grid laid out die by die (workgroup i runs on die
+// i % 8): all blocks of a (prompt, kv head) pair -- its query-head groups times its query tiles -- run back to
+// back on ONE die, so that pair's K/V is fetched from HBM once and then served from that die's L2 (the K/V
+// of a whole chunk does not fit an L2, and in plain order every die would stream all of it).
+template <typename T, int NH>
 __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__restrict__ q,
                                                                     const int32_t *__restrict__ cu_rows,
                                                                     const int32_t *__restrict__ prompt_slot, int hq,
                                                                     KvGeom kv, int layer, int n_prompts, int n_qt,
                                                                     T *__restrict__ out) {
-    const int rep_h = hq / kv.n_kv_heads, items = rep_h * n_qt;
+    const int rep_h = hq / kv.n_kv_heads, items = (rep_h / NH) * n_qt;
     const int b = blockIdx.x, die = b % 8, j = b / 8;
     const int unit = (j / items) * 8 + die;                      // (prompt, kv head)
     if (unit >= n_prompts * kv.n_kv_heads) return;
     const int item = j % items;
     const int p = unit / kv.n_kv_heads;
-    const int head = (unit % kv.n_kv_heads) * rep_h + item / n_qt;
+    const int kvh = unit % kv.n_kv_heads;
+    const int head0 = kvh * rep_h + (item / n_qt) * NH;          // first of this wave's NH heads
     const int q0 = (n_qt - 1 - item % n_qt) * 16;                // long causal ranges first
     const int row0 = cu_rows[p], len = cu_rows[p + 1] - row0;
     if (q0 >= len) return;
     const int lane = threadIdx.x, i = lane % 16, g = lane / 16;
     const int slot = prompt_slot[p];
-    const int kvh = head / (hq / kv.n_kv_heads);
     const T *head_base = (const T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
     const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
     const bool col_ok = (q0 + i) < len;
-    typename Mma<T>::frag qf[4];
+    typename Mma<T>::frag qf[NH][4];
+    AttnState st[NH];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-        if (col_ok)
-            qf[kk] = ld_frag(q + ((int64_t)(row0 + q0 + i) * hq + head) * HD + 32 * kk + 8 * g);
-        else
-            qf[kk] = zero_frag<T>();
+    for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (col_ok)
+                qf[h][kk] = ld_frag(q + ((int64_t)(row0 + q0 + i) * hq + head0 + h) * HD + 32 * kk + 8 * g);
+            else
+                qf[h][kk] = zero_frag<T>();
+        }
+        state_init(st[h]);
     }
-    AttnState st;
-    state_init(st);
     const int tok_end = min(q0 + 16, len);
-    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, 0, 32, tok_end, col_ok ? q0 + i : -1,
-                 LOG2E / sqrtf((float)HD), st);
-    float l = st.l;
-    l += __shfl_xor(l, 16, WAVE);
-    l += __shfl_xor(l, 32, WAVE);
+    attend_tiles<T, NH>(head_base, kv.block_elems(), table, kv.block_size, qf, 0, 32, tok_end, col_ok ? q0 + i : -1,
+                        LOG2E / sqrtf((float)HD), st);
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int col = 4 * g + v;
-        const float lc = __shfl(l, col, WAVE);
-        if (q0 + col < len) {
-            const float inv = 1.0f / lc;
-            T *o = out + ((int64_t)(row0 + q0 + col) * hq + head) * HD;
+    for (int h = 0; h < NH; ++h) {
+        float l = st[h].l;
+        l += __shfl_xor(l, 16, WAVE);
+        l += __shfl_xor(l, 32, WAVE);
 #pragma unroll
-            for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = from_f32<T>(st.o[nn][v] * inv);
+        for (int v = 0; v < 4; ++v) {
+            const int col = 4 * g + v;
+            const float lc = __shfl(l, col, WAVE);
+            if (q0 + col < len) {
+                const float inv = 1.0f / lc;
+                T *o = out + ((int64_t)(row0 + q0 + col) * hq + head0 + h) * HD;
+#pragma unroll
+                for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = from_f32<T>(st[h].o[nn][v] * inv);
+            }
         }
     }
+}
+
+template <typename T, int NH>
+static void prefill_launch(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts, int max_len,
+                           int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+    const int n_qt = (max_len + 15) / 16, items = (hq / kv.n_kv_heads / NH) * n_qt;
+    const int units = n_prompts * kv.n_kv_heads;
+    const unsigned grid = (unsigned)((units + 7) / 8 * 8) * (unsigned)items;
+    attention_prefill_mfma_kernel<T, NH><<<grid, 64, 0, s>>>((const T *)q, cu_rows, prompt_slot, hq, kv, layer, n_prompts,
+                                                             n_qt, (T *)out);
+}
+
+template <typename T>
+static void prefill_launch_t(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
+                             int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+    const int rep = hq / kv.n_kv_heads;   // heads per wave: as many as divide the group, up to three
+    if (rep % 3 == 0) prefill_launch<T, 3>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
+    else if (rep % 2 == 0) prefill_launch<T, 2>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
+    else prefill_launch<T, 1>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
 }
 
 void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
                                    int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
     if (n_prompts <= 0 || max_len <= 0) return;
-    const int n_qt = (max_len + 15) / 16, items = (hq / kv.n_kv_heads) * n_qt;
-    const int units = n_prompts * kv.n_kv_heads;
-    const unsigned grid = (unsigned)((units + 7) / 8 * 8) * (unsigned)items;
-    if (dtype == KD_BF16)
-        attention_prefill_mfma_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
-                                                                  n_prompts, n_qt, (bf16_t *)out);
-    else
-        attention_prefill_mfma_kernel<f16_t><<<grid, 64, 0, s>>>((const f16_t *)q, cu_rows, prompt_slot, hq, kv, layer,
-                                                                 n_prompts, n_qt, (f16_t *)out);
+    if (dtype == KD_BF16) prefill_launch_t<bf16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
+    else prefill_launch_t<f16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
 }
 
 // ---------------------------------------------------------------- decode
@@ -344,19 +371,20 @@ __global__ __launch_bounds__(64 * NW) void attention_decode_mfma_kernel(const T 
     const int rep = hq / kv.n_kv_heads;
     const T *head_base = (const T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)kvh * kv.head_elems();
     const int32_t *table = kv.block_table + (int64_t)slot * kv.max_blocks_per_slot;
-    typename Mma<T>::frag qf[4];
+    typename Mma<T>::frag qf[1][4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) {
         if (i < rep)
-            qf[kk] = ld_frag(q + ((int64_t)r * hq + kvh * rep + i) * HD + 32 * kk + 8 * g);
+            qf[0][kk] = ld_frag(q + ((int64_t)r * hq + kvh * rep + i) * HD + 32 * kk + 8 * g);
         else
-            qf[kk] = zero_frag<T>();
+            qf[0][kk] = zero_frag<T>();
     }
-    AttnState st;
-    state_init(st);
+    AttnState st1[1];
+    state_init(st1[0]);
+    AttnState &st = st1[0];
     const float scale_log2 = LOG2E / sqrtf((float)HD);
-    attend_tiles(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end, ctx - 1,
-                 scale_log2, st);
+    attend_tiles<T, 1>(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end, ctx - 1,
+                       scale_log2, st1);
     // ---- combine the waves
     float l = st.l;
     l += __shfl_xor(l, 16, WAVE);
