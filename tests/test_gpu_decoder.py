@@ -39,6 +39,11 @@ BF8 = workloads.scaled(C1, dtype="bf16", d_model=1024, n_q_heads=8, n_kv_heads=2
                        vocab=4096, n_layers=2, rope_theta=1.0e6).model
 BF4 = workloads.scaled(C1, dtype="bf16", d_model=512, n_q_heads=8, n_kv_heads=2, head_dim=128, d_ff=1024,
                        vocab=4096, n_layers=2, rope_theta=1.0e6).model
+# the head geometries of the 8B and 14B shapes: 8 kv heads with 4 and with 5 query heads each
+BF48 = workloads.scaled(C1, dtype="bf16", d_model=512, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ff=1024,
+                        vocab=2048, n_layers=2, rope_theta=1.0e6).model
+BF58 = workloads.scaled(C1, dtype="bf16", d_model=640, n_q_heads=40, n_kv_heads=8, head_dim=128, d_ff=1024,
+                        vocab=2048, n_layers=2, rope_theta=1.0e6).model
 
 
 def _teacher_forced(model, w, prompt, gen_tokens, gpu_logits, uid, seed, temperature, eos_id=-1, bias=0.0):
@@ -184,6 +189,9 @@ def test_bf16_plain_alu_path():
     (BF8, [100, 31], 3, 10, 64, 0.02, "bf16"),
     (BF8, [12] * 75, 4, 5, 64, 0.02, "f16"),              # 300 decode rows: 128-row GEMM blocks in threes, tall K slices
     (BF8, [12] * 105, 4, 4, 64, 0.02, "f16"),             # 420 decode rows: four 128-row blocks, BK 32
+    (BF48, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 32 query / 8 kv heads
+    (BF58, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 40 query / 8 kv heads: 5 per kv head, one head per prefill wave
+    (BF58, [20] * 40, 4, 5, 64, 0.02, "bf16"),            # 160 rows x 8 kv heads: the 4-wave decode blocks
 ])
 def test_bf16_matrix_core_path(model, lens, G, T, bs, std, act):
     say("bf16 model, matrix-core path, %s activations, lens=%s G=%d T=%d std=%g" % (act, lens[:6], G, T, std))
