@@ -109,6 +109,7 @@ def main():
     ap.add_argument("--binding-steps", type=int, default=4,
                     help="after the timed steps, also run this many sampling batches through the bound pipeline "
                          "(commit pass of step t-1 in one decode batch with the pilot pass of step t); 0 = skip")
+    ap.add_argument("--no-gemm-timing", action="store_true", help="skip the per-launch timing of the decode GEMMs")
     ap.add_argument("--no-score", action="store_true",
                     help="skip the scoring leg (pc_score over the last step's pilot rollouts)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -297,6 +298,38 @@ def main():
                              "rows": rows_s, "ms": round(dt_s * 1e3, 1), "TFLOPs": round(flops / dt_s / 1e12, 1),
                              "frac_mfma": round(flops / dt_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                              "mean_logprob": round(float(lp_out.mean().item()), 4)}
+    if not args.no_gemm_timing:
+        # per-launch time of the decode step's projection GEMMs at the pilot batch size (outside the timed region):
+        # a few eagerly launched decode steps with an event pair around every launch of one class, as for the
+        # attention figure above; priced against both rooflines (weights + activations in + result out, once each)
+        n = P * wl.n_pilot
+        qd, kvd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+        shapes = {"qkv": (pc.PC_KERNEL_GEMM_QKV, qd + 2 * kvd, m.d_model, 4), "wo": (pc.PC_KERNEL_GEMM_WO, m.d_model, qd, 4),
+                  "gate_up_swiglu": (pc.PC_KERNEL_GEMM_GATE_UP, 2 * m.d_ff, m.d_model, 1),
+                  "down": (pc.PC_KERNEL_GEMM_DOWN, m.d_model, m.d_ff, 4), "lm_head": (pc.PC_KERNEL_GEMM_LM_HEAD, m.vocab, m.d_model, 4)}
+        gem = {"rows": n}
+        with torch.cuda.stream(stream):
+            last = torch.empty((P, m.vocab), dtype=torch.float32, device=dev)
+            handles = pc.pc_prefill_shared(ctx, toks, cu, last, stream)
+            rows = np.repeat(np.arange(P, dtype=np.int32), wl.n_pilot)
+            seq_uids = (np.asarray(uids, np.int64)[:, None] * 65536 + np.arange(wl.n_pilot)[None, :]).reshape(-1)
+            for name, (cls, N, K, out_bytes) in shapes.items():
+                torch.cuda.synchronize()
+                pc.pc_timing_read(ctx, reset=True)
+                pc.generate(ctx, handles[rows], rows, last, seq_uids, 14, wl.temperature, wl.seed_sampler + 99, -1, 0.0,
+                            stream, time_class=cls, time_every=2)
+                torch.cuda.synchronize()
+                ms, cnt, ems, ecnt = pc.pc_timing_read(ctx, reset=True)
+                if cnt == 0:
+                    continue
+                us = max(ms / cnt - (ems / ecnt if ecnt else 0.0), 1e-6) * 1e3
+                byts = 2.0 * N * K + 2.0 * n * K + float(out_bytes) * n * N
+                flops = 2.0 * n * N * K
+                gem[name] = {"us": round(us, 2), "launches_timed": int(cnt), "GBps": round(byts / us / 1e3, 1),
+                             "frac_hbm": round(byts / us / 1e3 / HBM_PEAK_GBPS, 4), "TFLOPs": round(flops / us / 1e6, 1),
+                             "frac_mfma": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
+            pc.pc_release(ctx, handles, 1)
+        result["decode_gemms"] = gem
     if args.calibrate_copy:   # rocprofv3 --pmc runs scale FETCH_SIZE / WRITE_SIZE by what this copy reads
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
         dst = torch.empty_like(src)
