@@ -189,6 +189,8 @@ def test_bf16_plain_alu_path():
     (BF8, [100, 31], 3, 10, 64, 0.02, "bf16"),
     (BF8, [12] * 75, 4, 5, 64, 0.02, "f16"),              # 300 decode rows: 128-row GEMM blocks in threes, tall K slices
     (BF8, [12] * 105, 4, 4, 64, 0.02, "f16"),             # 420 decode rows: four 128-row blocks, BK 32
+    (BF, [70, 33, 300, 5, 256], 3, 10, 128, 0.02, "f16"), # larger KV blocks
+    (BF, [70, 33, 300, 5, 256], 3, 10, 256, 0.02, "f16"), # the largest block size the cache accepts
     (BF48, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 32 query / 8 kv heads
     (BF58, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 40 query / 8 kv heads: 5 per kv head, one head per prefill wave
     (BF58, [20] * 40, 4, 5, 64, 0.02, "bf16"),            # 160 rows x 8 kv heads: the 4-wave decode blocks
