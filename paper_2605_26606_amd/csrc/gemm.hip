@@ -133,7 +133,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     constexpr int STAGE_ELEMS = (BM + BN) * BK;
     static_assert(BK == 64 || BK == 32, "K tile");
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "whole passes");
-    static_assert(EPI != EPI_SWIGLU || (BN / WN) == 64, "SwiGLU needs one 64-wide gate/up chunk per wave");
+    static_assert(EPI != EPI_SWIGLU || (BN / WN) % 64 == 0, "SwiGLU needs whole 64-wide gate/up chunks per wave");
     static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     T *smem = (T *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
@@ -290,13 +290,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
         const int rbase = m0 + wm * (BM / WM) + i * 32 + row_l;
         if (EPI == EPI_SWIGLU) {
             T *C = (T *)Cv;
-            const int ncol = n0 + wn * 64;                 // start of this wave's gate/up chunk
-            const int ocol = (ncol / 64) * 32 + col_l;
-            if (ncol + 32 + col_l < N) {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int row = rbase + 8 * (v / 4) + (v % 4);
-                    if (row < M) C[(int64_t)row * (N / 2) + ocol] = from_f32<T>(silu_f(acc[i][0][v]) * acc[i][1][v]);
+            for (int p2 = 0; p2 < TN / 2; ++p2) {              // the wave's 64-wide chunks: 32 gate, 32 up columns
+                const int ncol = n0 + wn * (BN / WN) + 64 * p2;
+                const int ocol = (ncol / 64) * 32 + col_l;
+                if (ncol + 32 + col_l < N) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int row = rbase + 8 * (v / 4) + (v % 4);
+                        if (row < M)
+                            C[(int64_t)row * (N / 2) + ocol] =
+                                from_f32<T>(silu_f(acc[i][2 * p2][v]) * acc[i][2 * p2 + 1][v]);
+                    }
                 }
             }
         } else {
@@ -319,7 +324,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 
 template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> struct MfmaCfg {
     static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * BK * sizeof(T);
-    static constexpr bool swiglu_ok = (BN / WN == 64);
+    static constexpr bool swiglu_ok = ((BN / WN) % 64 == 0);
     template <int E> static void set_attr() {
         (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, E>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -363,6 +368,7 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> s
 
 template <typename T> static void gemm_init_t() {
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
+    MfmaCfg<T, 256, 256, 4, 2, 3, 32>::init();
     MfmaCfg<T, 128, 128, 2, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
     MfmaCfg<T, 128, 128, 2, 2, 2>::init();
@@ -401,6 +407,7 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
     typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
     typedef CfgTall CfgPrefill;
+    typedef MfmaCfg<T, 256, 256, 4, 2, 3, 32> CfgWide;      // wave tile 64x128: three fragment reads per four products
     typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
     typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 128, 128, 2, 2, 3, 32> CfgLarge3;    // BK 32, 48 KB of LDS: three blocks per CU
@@ -408,7 +415,11 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     typedef MfmaCfg<T, 256, 64, 4, 2, 3> CfgMidTall;        // the same for more than 256 rows
     typedef MfmaCfg<T, 64, 64, 2, 2, 4> CfgSmall;           // wave tile 32x32: many blocks for the small projections
     if (M > 512) {   // prefill: plenty of tiles
-        CfgPrefill::run(A, W, C, M, N, K, epi, 1, s);
+        // 256x256 tiles where they still come in several rounds per CU (the wide projections: +10 % measured);
+        // the narrow ones (1536 columns: 1.5 rounds of such tiles) keep 256x128
+        const int64_t wide_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
+        if (wide_tiles >= 2 * 256) CfgWide::run(A, W, C, M, N, K, epi, 1, s);
+        else CfgPrefill::run(A, W, C, M, N, K, epi, 1, s);
         return 1;
     }
     // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
