@@ -137,79 +137,117 @@ template <typename T> __device__ inline typename Mma<T>::frag zero_frag() {
     return __builtin_bit_cast(typename Mma<T>::frag, (u32x4){0, 0, 0, 0});
 }
 
-// Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end, for NH query-head groups
-// that share the kv head: the K and V fragments of a tile are loaded once and used for every group.
-// Tokens > col_limit (this lane's column) or >= tok_end are masked.
-template <typename T, int NH>
-__device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t block_elems,
-                                    const int32_t *__restrict__ table, int bs,
-                                    const typename Mma<T>::frag (&qf)[NH][4], int tile_begin, int tile_step, int tok_end,
-                                    int col_limit, float scale_log2, AttnState (&st)[NH]) {
+template <typename T> struct KvTile {
+    typename Mma<T>::frag ka[2][4], vf[8];
+};
+
+// The K and V fragments of the 32-token tile that starts at token t0 (lane layout as the products need it).
+template <typename T>
+__device__ inline void load_kv_tile(const T *__restrict__ head_base, int64_t block_elems,
+                                    const int32_t *__restrict__ table, int bs, int t0, KvTile<T> &kt) {
     const int lane = threadIdx.x % WAVE, i = lane % 16, g = lane / 16;
     const int krow = 8 * (i / 4) + (i % 4);   // tile u reads token krow + 4u: lane (column, g) then owns tokens 8g..8g+7
-    for (int t0 = tile_begin; t0 < tok_end; t0 += tile_step) {
-        const int tin = t0 % bs;
-        const T *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
-        const T *vb = kb + (int64_t)bs * HD;
-        typename Mma<T>::frag ka[2][4], vf[8];
+    const int tin = t0 % bs;
+    const T *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
+    const T *vb = kb + (int64_t)bs * HD;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kt.ka[u][kk] = ld_frag(kb + (int64_t)(tin + krow + 4 * u) * HD + 32 * kk + 8 * g);
+#pragma unroll
+    for (int nn = 0; nn < 8; ++nn) kt.vf[nn] = ld_frag(vb + (int64_t)(16 * nn + i) * bs + tin + 8 * g);
+}
+
+// One tile's update of the running softmax state of NH query-head groups that share the kv head.
+// Tokens > col_limit (this lane's column) or >= tok_end are masked.
+template <typename T, int NH>
+__device__ inline void attend_tile(const KvTile<T> &kt, const typename Mma<T>::frag (&qf)[NH][4], int t0, int tok_end,
+                                   int col_limit, float scale_log2, AttnState (&st)[NH]) {
+    const int lane = threadIdx.x % WAVE, g = lane / 16;
+    bool ok[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tok = t0 + 8 * g + 4 * u + v;
+            ok[u][v] = (tok <= col_limit) && (tok < tok_end);
+        }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        f32x4 s[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) s[u] = Mma<T>::m16(kt.ka[u][kk], qf[h][kk], s[u]);
+        }
+        // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
+        float mx = -INFINITY;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) ka[u][kk] = ld_frag(kb + (int64_t)(tin + krow + 4 * u) * HD + 32 * kk + 8 * g);
-#pragma unroll
-        for (int nn = 0; nn < 8; ++nn) vf[nn] = ld_frag(vb + (int64_t)(16 * nn + i) * bs + tin + 8 * g);
-        bool ok[2][4];
+            for (int v = 0; v < 4; ++v)
+                if (ok[u][v]) mx = fmaxf(mx, s[u][v]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
+        const float m_new = fmaxf(st[h].m, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float corr = exp2f((st[h].m - m_use) * scale_log2);   // st.m = -inf -> 0
+        float p[2][4], psum = 0.f;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int tok = t0 + 8 * g + 4 * u + v;
-                ok[u][v] = (tok <= col_limit) && (tok < tok_end);
+                p[u][v] = ok[u][v] ? exp2f((s[u][v] - m_use) * scale_log2) : 0.f;
+                psum += p[u][v];
             }
+        st[h].l = st[h].l * corr + psum;
+        st[h].m = m_new;
+        float c4[4];
 #pragma unroll
-        for (int h = 0; h < NH; ++h) {
-            f32x4 s[2];
+        for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
+        u32x4 pw = {pack2<T>(p[0][0], p[0][1]), pack2<T>(p[0][2], p[0][3]), pack2<T>(p[1][0], p[1][1]),
+                    pack2<T>(p[1][2], p[1][3])};
+        const typename Mma<T>::frag pa = __builtin_bit_cast(typename Mma<T>::frag, pw);
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                s[u] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int nn = 0; nn < 8; ++nn) {
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) s[u] = Mma<T>::m16(ka[u][kk], qf[h][kk], s[u]);
-            }
-            // lane (column i, g) holds the scores of tokens t0 + 8g + 4u + v
-            float mx = -INFINITY;
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    if (ok[u][v]) mx = fmaxf(mx, s[u][v]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, WAVE));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, WAVE));
-            const float m_new = fmaxf(st[h].m, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float corr = exp2f((st[h].m - m_use) * scale_log2);   // st.m = -inf -> 0
-            float p[2][4], psum = 0.f;
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    p[u][v] = ok[u][v] ? exp2f((s[u][v] - m_use) * scale_log2) : 0.f;
-                    psum += p[u][v];
-                }
-            st[h].l = st[h].l * corr + psum;
-            st[h].m = m_new;
-            float c4[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) c4[v] = __shfl(corr, 4 * g + v, WAVE);
-            u32x4 pw = {pack2<T>(p[0][0], p[0][1]), pack2<T>(p[0][2], p[0][3]), pack2<T>(p[1][0], p[1][1]),
-                        pack2<T>(p[1][2], p[1][3])};
-            const typename Mma<T>::frag pa = __builtin_bit_cast(typename Mma<T>::frag, pw);
-#pragma unroll
-            for (int nn = 0; nn < 8; ++nn) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) st[h].o[nn][v] *= c4[v];
-                st[h].o[nn] = Mma<T>::m16(pa, vf[nn], st[h].o[nn]);
-            }
+            for (int v = 0; v < 4; ++v) st[h].o[nn][v] *= c4[v];
+            st[h].o[nn] = Mma<T>::m16(pa, kt.vf[nn], st[h].o[nn]);
         }
+    }
+}
+
+// Consumes the 32-token tiles t0 = tile_begin, tile_begin + tile_step, ... < tok_end, for NH query-head groups
+// that share the kv head: the K and V fragments of a tile are loaded once and used for every group.
+// AHEAD: the next tile is requested before the current one is consumed (two fragment sets in registers);
+// pays where a wave has few tiles and nothing else on its SIMD hides their latency.
+template <typename T, int NH, bool AHEAD = false>
+__device__ inline void attend_tiles(const T *__restrict__ head_base, int64_t block_elems,
+                                    const int32_t *__restrict__ table, int bs,
+                                    const typename Mma<T>::frag (&qf)[NH][4], int tile_begin, int tile_step, int tok_end,
+                                    int col_limit, float scale_log2, AttnState (&st)[NH]) {
+    if (AHEAD) {
+        KvTile<T> a, b;
+        int ta = tile_begin;
+        if (ta >= tok_end) return;
+        load_kv_tile<T>(head_base, block_elems, table, bs, ta, a);
+        for (;;) {
+            const int tb = ta + tile_step;
+            if (tb < tok_end) load_kv_tile<T>(head_base, block_elems, table, bs, tb, b);
+            attend_tile<T, NH>(a, qf, ta, tok_end, col_limit, scale_log2, st);
+            if (tb >= tok_end) break;
+            ta = tb + tile_step;
+            if (ta < tok_end) load_kv_tile<T>(head_base, block_elems, table, bs, ta, a);
+            attend_tile<T, NH>(b, qf, tb, tok_end, col_limit, scale_log2, st);
+            if (ta >= tok_end) break;
+        }
+        return;
+    }
+    for (int t0 = tile_begin; t0 < tok_end; t0 += tile_step) {
+        KvTile<T> kt;
+        load_kv_tile<T>(head_base, block_elems, table, bs, t0, kt);
+        attend_tile<T, NH>(kt, qf, t0, tok_end, col_limit, scale_log2, st);
     }
 }
 
@@ -383,8 +421,8 @@ __global__ __launch_bounds__(64 * NW) void attention_decode_mfma_kernel(const T 
     state_init(st1[0]);
     AttnState &st = st1[0];
     const float scale_log2 = LOG2E / sqrtf((float)HD);
-    attend_tiles<T, 1>(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end, ctx - 1,
-                       scale_log2, st1);
+    attend_tiles<T, 1, NW == 8>(head_base, kv.block_elems(), table, kv.block_size, qf, beg + 32 * wave, ROUND, end,
+                                ctx - 1, scale_log2, st1);
     // ---- combine the waves
     float l = st.l;
     l += __shfl_xor(l, 16, WAVE);
