@@ -6,6 +6,8 @@
 //               double-buffered, one barrier per K tile
 #include <algorithm>
 
+#include <type_traits>
+
 #include "pc_internal.h"
 
 namespace pc {
@@ -119,14 +121,21 @@ template <int N> __device__ inline void wait_vmcnt_le() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK, int EPI>
+// M16: the products are 16x16x32 instructions (a: A[row l%16][k = 8*(l/16) .. +7], b likewise,
+// d[v]: D[row 4*(l/16) + v][col l%16]) instead of 32x32x16: the same fragment bytes per product volume, four
+// times as many accumulator tiles per wave.
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK, int EPI, bool M16 = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                         void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
                                                         int S, int plain) {
     constexpr int CPR = BK / 8;                           // 16-byte chunks per tile row
     constexpr int RPL = 64 / CPR;                         // tile rows one wave-wide load covers
     constexpr int SWZ_DIV = 16 / CPR;                     // rows that share a swizzle value
-    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+    constexpr int RT = M16 ? 16 : 32;                     // rows (columns) of one accumulator tile
+    constexpr int CG = 64 / RT;                           // 16-byte k chunks one product consumes per row
+    constexpr int AV = M16 ? 4 : 16;                      // accumulator values per lane and tile
+    constexpr int TM = BM / WM / RT, TN = BN / WN / RT;
+    typedef typename std::conditional<M16, f32x4_t, f32x16_t>::type acc_t;
     constexpr int NW = WM * WN;                           // waves per block
     constexpr int A_ITERS = BM / (RPL * NW), W_ITERS = BN / (RPL * NW);   // the waves move RPL*NW rows of BK k per pass
     constexpr int LOADS = A_ITERS + W_ITERS;              // load instructions per thread per K tile
@@ -206,40 +215,44 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pw[i] + koff),
                                                  (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
     };
-    f32x16_t acc[TM][TN];
+    acc_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int jj = 0; jj < TN; ++jj)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][jj][v] = 0.f;
+            for (int v = 0; v < AV; ++v) acc[i][jj][v] = 0.f;
 
-    // fragment addressing: lane (fr, fg) reads chunk 2*kk + fg of its row, stored at slot chunk ^ swz(row)
-    const int fr = lane % 32, fg = lane / 32;
+    // fragment addressing: lane (fr, fg) reads chunk CG*kk + fg of its row, stored at slot chunk ^ swz(row)
+    const int fr = lane % RT, fg = lane / RT;
     int arow[TM], aswz[TM], wrow[TN], wswz[TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        arow[i] = wm * (BM / WM) + i * 32 + fr;
+        arow[i] = wm * (BM / WM) + i * RT + fr;
         aswz[i] = (arow[i] / SWZ_DIV) & (CPR - 1);
     }
 #pragma unroll
     for (int jj = 0; jj < TN; ++jj) {
-        wrow[jj] = wn * (BN / WN) + jj * 32 + fr;
+        wrow[jj] = wn * (BN / WN) + jj * RT + fr;
         wswz[jj] = (wrow[jj] / SWZ_DIV) & (CPR - 1);
     }
     typedef typename Mma<T>::frag frag_t;
     auto load_frags = [&](const T *sa, const T *sw, int kk, frag_t (&fa)[TM], frag_t (&fb)[TN]) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[i] = *(const frag_t *)(sa + arow[i] * BK + (((2 * kk + fg) ^ aswz[i]) * 8));
+        for (int i = 0; i < TM; ++i) fa[i] = *(const frag_t *)(sa + arow[i] * BK + (((CG * kk + fg) ^ aswz[i]) * 8));
 #pragma unroll
-        for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const frag_t *)(sw + wrow[jj] * BK + (((2 * kk + fg) ^ wswz[jj]) * 8));
+        for (int jj = 0; jj < TN; ++jj) fb[jj] = *(const frag_t *)(sw + wrow[jj] * BK + (((CG * kk + fg) ^ wswz[jj]) * 8));
+    };
+    auto product = [&](frag_t a, frag_t b, acc_t c) -> acc_t {
+        if constexpr (M16) return Mma<T>::m16(a, b, c);
+        else return Mma<T>::m32(a, b, c);
     };
     auto compute = [&](int stage, int kt_next, int refill) {
         const T *sa = smem + stage * STAGE_ELEMS;
         const T *sw = sa + BM * BK;
         frag_t fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
         load_frags(sa, sw, 0, fa[0], fb[0]);
-        constexpr int KK = BK / 16;
+        constexpr int KK = BK / (8 * CG);
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             // this step's share of the refill: the loads are spread over the tile's compute steps
@@ -251,7 +264,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int jj = 0; jj < TN; ++jj)
-                    acc[i][jj] = Mma<T>::m32(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj]);
+                    acc[i][jj] = product(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj]);
             // instruction order asked of the compiler: after each matrix instruction one or two LDS fragment
             // reads and one global->LDS load, instead of all reads in a burst behind the last product
             // (measured: +5 % on the prefill shapes, neutral on the decode shapes)
@@ -283,6 +296,47 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     wait_vmcnt_le<0>();   // nothing may still be writing LDS when the block retires
 
     // ---- epilogue
+    if constexpr (M16) {   // lane (column lane%16, g = lane/16) holds rows 4g .. 4g+3 of each 16x16 tile
+        const int col_l = lane % 16, row_l = 4 * (lane / 16);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rbase = m0 + wm * (BM / WM) + i * 16 + row_l;
+            if (EPI == EPI_SWIGLU) {
+                T *C = (T *)Cv;
+#pragma unroll
+                for (int p2 = 0; p2 < TN / 4; ++p2)            // a 64-wide chunk = tiles 4p2, 4p2+1 (gate), 4p2+2, 4p2+3 (up)
+#pragma unroll
+                    for (int q = 0; q < 2; ++q) {
+                        const int ncol = n0 + wn * (BN / WN) + 64 * p2;
+                        const int ocol = (ncol / 64) * 32 + 16 * q + col_l;
+                        if (ncol + 32 + 16 * q + col_l < N) {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const int row = rbase + v;
+                                if (row < M)
+                                    C[(int64_t)row * (N / 2) + ocol] =
+                                        from_f32<T>(silu_f(acc[i][4 * p2 + q][v]) * acc[i][4 * p2 + 2 + q][v]);
+                            }
+                        }
+                    }
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < TN; ++jj) {
+                    const int col = n0 + wn * (BN / WN) + jj * 16 + col_l;
+                    if (col >= N) continue;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = rbase + v;
+                        if (row >= M) continue;
+                        if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
+                        if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
+                        if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(acc[i][jj][v]);
+                    }
+                }
+            }
+        }
+        return;
+    }
     const int col_l = lane % 32;
     const int row_l = 4 * (lane / 32);
 #pragma unroll
@@ -322,11 +376,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     }
 }
 
-template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> struct MfmaCfg {
+template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64, bool M16 = false> struct MfmaCfg {
     static constexpr size_t smem = (size_t)NSTAGE * (BM + BN) * BK * sizeof(T);
     static constexpr bool swiglu_ok = ((BN / WN) % 64 == 0);
     template <int E> static void set_attr() {
-        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, E>,
+        (void)hipFuncSetAttribute((const void *)gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, E, M16>,
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     }
     static void init() {
@@ -343,13 +397,13 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> s
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
             case EPI_SWIGLU:
                 if constexpr (swiglu_ok)
-                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
                 break;
-            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
         }
     }
     // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
@@ -368,7 +422,8 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64> s
 
 template <typename T> static void gemm_init_t() {
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
-    MfmaCfg<T, 256, 256, 4, 2, 3, 32>::init();
+    MfmaCfg<T, 256, 256, 4, 2, 3, 32, true>::init();
+    MfmaCfg<T, 256, 128, 4, 2, 3, 64, true>::init();
     MfmaCfg<T, 128, 128, 2, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
     MfmaCfg<T, 128, 128, 2, 2, 2>::init();
@@ -406,8 +461,10 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
                               size_t slice_cap_floats, hipStream_t s) {
     // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
     typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
-    typedef CfgTall CfgPrefill;
-    typedef MfmaCfg<T, 256, 256, 4, 2, 3, 32> CfgWide;      // wave tile 64x128: three fragment reads per four products
+    // prefill: 16x16x32 products (measured +3 to +12 % over 32x32x16 at 16384 rows, nothing at decode sizes;
+    // the results are bit-identical)
+    typedef MfmaCfg<T, 256, 128, 4, 2, 3, 64, true> CfgPrefill;
+    typedef MfmaCfg<T, 256, 256, 4, 2, 3, 32, true> CfgWide;   // wave tile 64x128: three fragment reads per four products
     typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
     typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 128, 128, 2, 2, 3, 32> CfgLarge3;    // BK 32, 48 KB of LDS: three blocks per CU
