@@ -130,7 +130,9 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                                                         int S, int plain) {
     constexpr int CPR = BK / 8;                           // 16-byte chunks per tile row
     constexpr int RPL = 64 / CPR;                         // tile rows one wave-wide load covers
-    constexpr int SWZ_DIV = 16 / CPR;                     // rows that share a swizzle value
+    // rows that share a swizzle value (measured with a read-rate probe: 16-row fragment reads of 64-byte
+    // rows want a new value every 2 rows, 267 -> 320 GB/s per CU)
+    constexpr int SWZ_DIV = (M16 && BK == 32) ? 2 : 16 / CPR;
     constexpr int RT = M16 ? 16 : 32;                     // rows (columns) of one accumulator tile
     constexpr int CG = 64 / RT;                           // 16-byte k chunks one product consumes per row
     constexpr int AV = M16 ? 4 : 16;                      // accumulator values per lane and tile
