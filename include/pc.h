@@ -42,12 +42,16 @@ typedef int32_t pc_status;
 
 /* Type of the activations, the KV cache and the library's own weight copies of a bf16 model. */
 #define PC_ACT_DEFAULT 0 /* = PC_ACT_F16 */
-#define PC_ACT_BF16 1    /* bfloat16 throughout */
+#define PC_ACT_BF16 1    /* bfloat16 throughout.  OUTSIDE the 2e-2 logit acceptance bound for deep models: every
+                            rounding point loses 2^-9 relative, and over a 28-layer decoder the logits drift by up
+                            to 1e-1 (measured 7.5e-2 on the 1.5B shape).  Kept for callers that need the bf16
+                            exponent range; tested against its own bound of 1.5e-1 x max(1, max|logit|). */
 #define PC_ACT_F16 2     /* IEEE half: the bf16 weights convert to half without loss (below 6.1e-5 in magnitude
                             with an absolute error under 3e-8); activations carry 11 significand bits instead of
                             8 at the same matrix-core rate, which keeps the logits of a 28-layer model within
-                            1e-2 of exact arithmetic where bf16 activations drift by 6e-2.  Values beyond the
-                            half range (65504) saturate. */
+                            1e-2 of exact arithmetic.  This is the type the 2e-2 acceptance bound is met with.
+                            Values beyond the half range (65504) SATURATE to +-65504 (never inf/NaN) and every
+                            saturated store is counted: see pc_saturation_count. */
 
 typedef struct pc_ctx pc_ctx;
 
@@ -126,6 +130,11 @@ pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value);
  * bracket itself costs).  SYNCHRONISES on the recorded events.  reset != 0 recycles them. */
 pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, double *empty_ms,
                          int64_t *empty_pairs, int32_t reset);
+/* Number of activation / KV-cache values that were clamped to +-65504 on their way into IEEE half since
+ * the last reset (PC_ACT_F16 contexts; always 0 otherwise).  A non-zero count means the model's activations
+ * leave the half range and the logits are no longer trustworthy: use PC_ACT_BF16 for such a model.
+ * `count` is a host pointer.  SYNCHRONISES the device. */
+pc_status pc_saturation_count(pc_ctx *ctx, int64_t *count, int32_t reset);
 /* Number of free KV blocks / total KV blocks (host bookkeeping, no GPU work). */
 pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks);
 
@@ -160,7 +169,8 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
  *   logits     device fp32 [n, vocab]
  * With PC_OPT_USE_GRAPH the step is captured once per (sequence list,
  * pointers, stream) and replayed; keep the pointers stable across steps.
- * A sequence that has used up its reserved tokens is PC_ERR_INVALID_ARG. */
+ * A sequence that already holds prompt length + max_new_tokens tokens (the
+ * reservation of its pc_fork) is PC_ERR_INVALID_ARG. */
 pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n,
                          float *logits, void *stream);
 
@@ -197,11 +207,24 @@ pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, c
  *   tokens_out  device int32 [n]
  *   logprob_out device fp32 [n] or NULL: log-probability of the sampled token
  *   finished    device uint8 [n] or NULL, in/out: set when eos_id is sampled;
- *               a row already finished on entry yields eos_id and logprob 0. */
+ *               a row already finished on entry yields eos_id and logprob 0.
+ *   top_p       in (0, 1]: nucleus sampling (Section 4.2 names top_p = 1.0 for
+ *               training).  Below 1 only the smallest set of tokens whose
+ *               probability mass reaches top_p is sampled from: tokens in
+ *               order of decreasing probability (ties: lower id first) until
+ *               their cumulative mass is >= top_p; the inverse CDF then runs
+ *               over the kept tokens in id order, and logprob_out is the
+ *               log-probability under the renormalised kept set.
+ *   hist_tokens, hist_logprob  device [>= max index + 1] or NULL: second
+ *               destinations of the token / log-probability of row i, at index
+ *               hist_index[i] (device int32 [n]; NULL: index i).  Lets a
+ *               caller keep a [step][sequence] history without a copy kernel
+ *               per step while its decode batch shrinks. */
 pc_status pc_sample(const float *logits, const int32_t *logit_row, int32_t n, int32_t vocab,
-                    float temperature, uint64_t seed, const uint64_t *seq_uid, const int32_t *step,
+                    float temperature, float top_p, uint64_t seed, const uint64_t *seq_uid, const int32_t *step,
                     int32_t step_base, int32_t eos_id, float eos_logit_bias, int32_t *tokens_out,
-                    float *logprob_out, uint8_t *finished, void *stream);
+                    float *logprob_out, uint8_t *finished, int32_t *hist_tokens, float *hist_logprob,
+                    const int32_t *hist_index, void *stream);
 
 /* Per-prompt reward statistics (Eq. 3; Section 3.3 pilot success rate
  * p_hat = (1/n) sum r_j, Var = p(1-p) for binary rewards).

@@ -81,7 +81,8 @@ def library() -> C.CDLL:
             "pc_decode_step": [vp, vp, vp, i32, vp, vp],
             "pc_release": [vp, vp, i32, i32],
             "pc_score": [vp, vp, vp, vp, i32, f32, vp, vp],
-            "pc_sample": [vp, vp, i32, i32, f32, u64, vp, vp, i32, i32, f32, vp, vp, vp, vp],
+            "pc_sample": [vp, vp, i32, i32, f32, f32, u64, vp, vp, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp],
+            "pc_saturation_count": [vp, C.POINTER(i64), i32],
             "pc_group_stats": [vp, vp, i32, vp, vp, vp, vp, vp],
             "pc_select_commit": [vp, i32, f32, f32, f32, i32, vp, vp, vp, vp, vp, vp],
             "pc_advantages": [vp, vp, i32, f32, vp, vp, vp, vp],
@@ -139,7 +140,9 @@ class Context:
         lib = library()
         self.model = model
         self.vocab = int(model.vocab)
-        self._weights = weights
+        # the library copies the per-layer matrices into its own layout: only these three must outlive the
+        # context (the caller is free to drop its per-layer tensors after this constructor returns)
+        self._weights = {k: weights[k] for k in ("tok_embed", "lm_head", "final_norm")}
         mc = _ModelConfig(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
                           model.d_ff, model.vocab, model.rms_eps, model.rope_theta, _DTYPES[model.dtype],
                           {"default": 0, "bf16": 1, "f16": 2}[act_dtype])
@@ -162,6 +165,7 @@ class Context:
         h = C.c_void_p()
         _check(lib.pc_create(C.byref(mc), C.byref(w), C.byref(cc), C.byref(h)))
         self._h = h
+        self._arrays = None
 
     @property
     def handle(self):
@@ -192,6 +196,14 @@ def pc_timing_read(ctx: Context, reset: bool = True):
     _check(library().pc_timing_read(ctx.handle, C.byref(ms), C.byref(n), C.byref(ems), C.byref(en),
                                     1 if reset else 0))
     return ms.value, n.value, ems.value, en.value
+
+
+def pc_saturation_count(ctx: Context, reset: bool = False) -> int:
+    """Values clamped to the IEEE-half range on their way into activations or the KV cache since the last
+    reset (0 unless the model's activations leave +-65504); synchronises the device."""
+    n = C.c_int64()
+    _check(library().pc_saturation_count(ctx.handle, C.byref(n), 1 if reset else 0))
+    return n.value
 
 
 def pc_kv_blocks(ctx: Context):
@@ -261,19 +273,28 @@ def pc_release(ctx: Context, ids, kind: int):
 def pc_sample(logits: torch.Tensor, logit_row: Optional[torch.Tensor], n: int, vocab: int, temperature: float,
               seed: int, seq_uid: torch.Tensor, step: Optional[torch.Tensor], step_base: int, eos_id: int,
               eos_logit_bias: float, tokens_out: torch.Tensor, logprob_out: Optional[torch.Tensor] = None,
-              finished: Optional[torch.Tensor] = None, stream=None):
+              finished: Optional[torch.Tensor] = None, stream=None, top_p: float = 1.0,
+              hist_tokens: Optional[torch.Tensor] = None, hist_logprob: Optional[torch.Tensor] = None,
+              hist_index: Optional[torch.Tensor] = None):
     for t, name in ((seq_uid, "seq_uid"), (tokens_out, "tokens_out"), (logit_row, "logit_row"), (step, "step"),
-                    (logprob_out, "logprob_out"), (finished, "finished")):
+                    (logprob_out, "logprob_out"), (finished, "finished"), (hist_index, "hist_index")):
         if t is not None and t.numel() < n:
             raise ValueError("%s has fewer than n entries" % name)
+    if hist_index is None:
+        for t, name in ((hist_tokens, "hist_tokens"), (hist_logprob, "hist_logprob")):
+            if t is not None and t.numel() < n:
+                raise ValueError("%s has fewer than n entries" % name)
     if logit_row is None and logits.numel() < n * vocab:
         raise ValueError("logits has fewer than n rows")
     _check(library().pc_sample(_dev(logits, torch.float32, "logits"), _dev(logit_row, torch.int32, "logit_row"),
-                               int(n), int(vocab), float(temperature), int(seed) & (2 ** 64 - 1),
+                               int(n), int(vocab), float(temperature), float(top_p), int(seed) & (2 ** 64 - 1),
                                _dev(seq_uid, torch.int64, "seq_uid"), _dev(step, torch.int32, "step"), int(step_base),
                                int(eos_id), float(eos_logit_bias), _dev(tokens_out, torch.int32, "tokens_out"),
                                _dev(logprob_out, torch.float32, "logprob_out"),
-                               _dev(finished, torch.uint8, "finished"), _stream_ptr(stream)))
+                               _dev(finished, torch.uint8, "finished"),
+                               _dev(hist_tokens, torch.int32, "hist_tokens"),
+                               _dev(hist_logprob, torch.float32, "hist_logprob"),
+                               _dev(hist_index, torch.int32, "hist_index"), _stream_ptr(stream)))
 
 
 def pc_group_stats(rewards: torch.Tensor, group_off: torch.Tensor, n_pos=None, n_tot=None, mean=None, var=None,

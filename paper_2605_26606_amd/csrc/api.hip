@@ -26,8 +26,71 @@ struct Slot {
     bool is_prompt = false;
     int len = 0;          // tokens whose K/V are in the cache
     int capacity = 0;     // tokens the slot's blocks can hold
+    int limit = 0;        // tokens the slot may hold: prompt length + reserved new tokens, at most max_ctx
     int prompt = -1;      // sequences: the prompt slot they were forked from
     std::vector<int32_t> blocks;
+};
+
+// Pinned host staging for the small control arrays that go to the device (block-table rows, row
+// metadata, sequence lists).  An asynchronous copy reads its host source when the stream reaches it, so
+// the source must stay untouched until then: every upload is copied into a fresh piece of a pinned ring
+// first, and a piece is reused only after an event recorded behind its copies has completed.
+struct Staging {
+    static constexpr int N_FENCE = 16;
+    char *base = nullptr;
+    size_t cap = 0, head = 0, open_begin = 0;
+    struct Fence {
+        size_t begin = 0, end = 0;
+        hipEvent_t ev = nullptr;
+        bool pending = false;
+    } fences[N_FENCE];
+    int next_fence = 0;
+
+    pc_status init(size_t bytes) {
+        cap = (bytes + 4095) / 4096 * 4096;
+        PC_HIP(hipHostMalloc((void **)&base, cap, hipHostMallocDefault));
+        for (Fence &f : fences) PC_HIP(hipEventCreateWithFlags(&f.ev, hipEventDisableTiming));
+        return PC_OK;
+    }
+    void destroy() {
+        for (Fence &f : fences)
+            if (f.ev) (void)hipEventDestroy(f.ev);
+        if (base) (void)hipHostFree(base);
+        base = nullptr;
+    }
+    // closes the pieces handed out since the last mark: they are free again once `st` has passed this point
+    pc_status mark(hipStream_t st) {
+        if (head == open_begin) return PC_OK;
+        Fence &f = fences[next_fence];
+        next_fence = (next_fence + 1) % N_FENCE;
+        if (f.pending) PC_HIP(hipEventSynchronize(f.ev));
+        f.begin = open_begin;
+        f.end = head;
+        PC_HIP(hipEventRecord(f.ev, st));
+        f.pending = true;
+        open_begin = head;
+        return PC_OK;
+    }
+    // dst (device) <- src (host, n bytes) on stream st, through the ring
+    pc_status push(void *dst, const void *src, size_t n, hipStream_t st) {
+        if (n == 0) return PC_OK;
+        const size_t need = (n + 63) / 64 * 64;
+        if (need > cap / 2) PC_FAIL(PC_ERR_OOM, "staging: one upload of %zu bytes exceeds the ring", n);
+        if (head + need > cap) {   // wrap: everything handed out so far has been enqueued on st
+            pc_status rc = mark(st);
+            if (rc != PC_OK) return rc;
+            head = open_begin = 0;
+        }
+        for (Fence &f : fences)
+            if (f.pending && f.begin < head + need && head < f.end) {
+                PC_HIP(hipEventSynchronize(f.ev));
+                f.pending = false;
+            }
+        memcpy(base + head, src, n);
+        PC_HIP(hipMemcpyAsync(dst, base + head, n, hipMemcpyHostToDevice, st));
+        head += need;
+        return PC_OK;
+    }
 };
 
 }  // namespace pc
@@ -64,6 +127,12 @@ struct pc_ctx {
     int32_t *d_dec_slot = nullptr;
     float *slices = nullptr;       // split-K slices of the decode projections
     size_t slice_cap = 0;
+    // the scratch the layer kernels use right now: the context's own buffers, or the static device array
+    // of the entry point that allocates nothing
+    float *cur_slices = nullptr, *cur_attn_scratch = nullptr;
+    size_t cur_slice_cap = 0;
+    uint32_t *d_sat = nullptr;     // stores clamped to the half range (KD_F16)
+    Staging stage;
     std::vector<int32_t> dec_seq;     // sequence list currently resident in d_dec_slot
     int dec_group = 1;                // consecutive entries of dec_seq that share a prompt
     std::vector<int32_t> stamp;
@@ -123,18 +192,23 @@ void free_all(pc_ctx *ctx) {
     for (auto p : ctx->ffn_norm) fr(p);
     fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
     fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->score_logits); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
-    fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices); fr(ctx->lm_head_copy);
+    fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices); fr(ctx->lm_head_copy); fr(ctx->d_sat);
+    ctx->stage.destroy();
 }
 
 // uploads rows [s0, s1] of the host block table and slot lengths
 pc_status upload_slots(pc_ctx *ctx, int s0, int s1, hipStream_t st) {
     if (s1 < s0) return PC_OK;
     const size_t w = ctx->max_blocks_per_slot;
-    PC_HIP(hipMemcpyAsync(ctx->d_block_table + (size_t)s0 * w, ctx->h_table.data() + (size_t)s0 * w,
-                          (size_t)(s1 - s0 + 1) * w * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    PC_HIP(hipMemcpyAsync(ctx->d_slot_len + s0, ctx->h_len.data() + s0, (size_t)(s1 - s0 + 1) * sizeof(int32_t),
-                          hipMemcpyHostToDevice, st));
-    return PC_OK;
+    // in pieces: a single upload may not exceed half of the staging ring
+    const int per = std::max<int>(1, (int)(ctx->stage.cap / 4 / (w * sizeof(int32_t))));
+    for (int a = s0; a <= s1; a += per) {
+        const int b = std::min(s1, a + per - 1);
+        pc_status rc = ctx->stage.push(ctx->d_block_table + (size_t)a * w, ctx->h_table.data() + (size_t)a * w,
+                                       (size_t)(b - a + 1) * w * sizeof(int32_t), st);
+        if (rc != PC_OK) return rc;
+    }
+    return ctx->stage.push(ctx->d_slot_len + s0, ctx->h_len.data() + s0, (size_t)(s1 - s0 + 1) * sizeof(int32_t), st);
 }
 
 void write_table_row(pc_ctx *ctx, int slot) {
@@ -188,50 +262,53 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
     const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     const KvGeom kv = ctx->geom();
     const int n_splits = attention_decode_splits(rows, m.n_kv_heads, ctx->c.max_ctx);
+    uint32_t *sat = ctx->d_sat;
     int pending = 1;
     for (int l = 0; l < m.n_layers; ++l) {
-        launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending,
-                       st);
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, pending,
+                       sat, st);
         int s_qkv;
         {
             Timed t(ctx, PC_KERNEL_GEMM_QKV, st);
             s_qkv = launch_gemm(dt, impl, ctx->a, ctx->wqkv[l], ctx->qkv, rows, qd + 2 * kvd, m.d_model, EPI_STORE_F32,
-                                ctx->slices, ctx->slice_cap, st);
+                                ctx->cur_slices, ctx->cur_slice_cap, sat, st);
         }
-        launch_rope_append(dt, s_qkv > 1 ? ctx->slices : ctx->qkv, s_qkv, row_slot, row_pos, ctx->d_slot_len,
-                           ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, st);
+        launch_rope_append(dt, s_qkv > 1 ? ctx->cur_slices : ctx->qkv, s_qkv, row_slot, row_pos, ctx->d_slot_len,
+                           ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, sat, st);
         if (ctx->mfma_attention()) {
             if (row_pos)
                 launch_attention_prefill_mfma(dt, ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
-                                              ctx->attn, st);
+                                              ctx->attn, sat, st);
             else {
                 {
                     Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
                     launch_attention_decode_mfma(dt, ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
-                                                 ctx->dec_group, ctx->attn_scratch, ctx->attn, st);
+                                                 ctx->dec_group, ctx->cur_attn_scratch, ctx->attn, sat, st);
                 }
                 launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, m.n_kv_heads, n_splits,
-                                              ctx->attn_scratch, ctx->attn, st);
+                                              ctx->cur_attn_scratch, ctx->attn, sat, st);
             }
         } else {
             launch_attention_simt(dt, ctx->q, row_slot, row_pos, ctx->d_slot_len, rows, m.n_q_heads, kv, l, ctx->attn,
-                                  st);
+                                  sat, st);
         }
         int s_wo;
         {
             Timed t(ctx, PC_KERNEL_GEMM_WO, st);
-            s_wo = launch_gemm(dt, impl, ctx->attn, ctx->wo[l], ctx->h, rows, m.d_model, qd, EPI_RESID_F32, ctx->slices,
-                               ctx->slice_cap, st);
+            s_wo = launch_gemm(dt, impl, ctx->attn, ctx->wo[l], ctx->h, rows, m.d_model, qd, EPI_RESID_F32, ctx->cur_slices,
+                               ctx->cur_slice_cap, sat, st);
         }
-        launch_rmsnorm(dt, ctx->h, nullptr, ctx->ffn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->slices, s_wo, st);
+        launch_rmsnorm(dt, ctx->h, nullptr, ctx->ffn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, s_wo, sat,
+                       st);
         {
             Timed t(ctx, PC_KERNEL_GEMM_GATE_UP, st);
-            launch_gemm(dt, impl, ctx->a, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU, nullptr, 0, st);
+            launch_gemm(dt, impl, ctx->a, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU, nullptr, 0, sat,
+                        st);
         }
         {
             Timed t(ctx, PC_KERNEL_GEMM_DOWN, st);
             pending = launch_gemm(dt, impl, ctx->act, ctx->wdown[l], ctx->h, rows, m.d_model, m.d_ff, EPI_RESID_F32,
-                                  ctx->slices, ctx->slice_cap, st);
+                                  ctx->cur_slices, ctx->cur_slice_cap, sat, st);
         }
     }
     return pending;
@@ -241,11 +318,12 @@ void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits,
     const pc_model_config &m = ctx->m;
     launch_embed(ctx->kd, ctx->tok_embed, tokens_in, n, m.d_model, m.vocab, ctx->h, st);
     const int pending = enqueue_layers(ctx, n, ctx->d_dec_slot, nullptr, nullptr, nullptr, 0, 0, st);
-    launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, ctx->slices, pending, st);
+    launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, n, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, pending,
+                   ctx->d_sat, st);
     {
         Timed t(ctx, PC_KERNEL_GEMM_LM_HEAD, st);
         launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, logits, n, m.vocab, m.d_model, EPI_STORE_F32, nullptr, 0,
-                    st);
+                    ctx->d_sat, st);
     }
     launch_advance_len(ctx->d_slot_len, ctx->d_dec_slot, n, st);
 }
@@ -411,6 +489,15 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
                   attention_decode_scratch_floats(std::min<int>((int)R, cache->max_slots), m.n_q_heads, m.head_dim)));
     ctx->slice_cap = (size_t)8 << 20;   // 32 MB
     TRY(dev_alloc(&ctx->slices, ctx->slice_cap));
+    ctx->cur_slices = ctx->slices;
+    ctx->cur_slice_cap = ctx->slice_cap;
+    ctx->cur_attn_scratch = ctx->attn_scratch;
+    TRY(dev_alloc(&ctx->d_sat, 1));
+    TRY_HIP(hipMemsetAsync(ctx->d_sat, 0, sizeof(uint32_t), st));
+    // staging ring: four times the largest set of control arrays one call uploads
+    TRY(ctx->stage.init(4 * ((2 * R + 8 * (size_t)cache->max_slots + 64) * sizeof(int32_t) +
+                             (size_t)cache->max_slots * (ctx->max_blocks_per_slot + 1) * sizeof(int32_t))));
+    ctx->dec_seq.reserve((size_t)cache->max_slots);
     TRY(dev_alloc(&ctx->d_meta, 2 * R + 3 * (size_t)cache->max_slots + 2 * (size_t)cache->max_slots + 16));
     TRY(dev_alloc(&ctx->d_dec_slot, (size_t)cache->max_slots));
     TRY_HIP(hipDeviceSynchronize());
@@ -471,6 +558,16 @@ pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, doubl
     return PC_OK;
 }
 
+pc_status pc_saturation_count(pc_ctx *ctx, int64_t *count, int32_t reset) {
+    if (!ctx || !count) PC_FAIL(PC_ERR_INVALID_ARG, "pc_saturation_count: null argument");
+    uint32_t v = 0;
+    PC_HIP(hipDeviceSynchronize());
+    PC_HIP(hipMemcpy(&v, ctx->d_sat, sizeof(v), hipMemcpyDeviceToHost));
+    if (reset) PC_HIP(hipMemset(ctx->d_sat, 0, sizeof(v)));
+    *count = (int64_t)v;
+    return PC_OK;
+}
+
 pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks) {
     if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_kv_blocks: null context");
     if (free_blocks) *free_blocks = (int64_t)ctx->free_blocks.size();
@@ -489,10 +586,13 @@ struct ScoreRequest {
 // prompt slot and KV blocks per sequence, runs the layers in chunks of whole sequences, and then either
 // writes the last row's logits of every sequence (last_logits) or the log-probabilities of the completion
 // tokens (score).
+static pc_status forward_chunks(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
+                                const int32_t *handle_out, float *last_logits, const ScoreRequest *score, int smin,
+                                int smax, hipStream_t st);
+
 static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
                                    int32_t *handle_out, float *last_logits, const ScoreRequest *score,
                                    hipStream_t st) {
-    const pc_model_config &m = ctx->m;
     const int bs = ctx->c.block_size;
     if (cu_lens[0] != 0) PC_FAIL(PC_ERR_INVALID_ARG, "forward: cu_lens[0] must be 0");
     int64_t need_blocks = 0;
@@ -520,6 +620,7 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
         s.len = len;
         const int nb = (len + bs - 1) / bs;
         s.capacity = nb * bs;
+        s.limit = len;
         for (int i = 0; i < nb; ++i) {
             const int32_t b = ctx->free_blocks.back();
             ctx->free_blocks.pop_back();
@@ -531,6 +632,21 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
         smin = std::min(smin, slot);
         smax = std::max(smax, slot);
     }
+    pc_status rc = forward_chunks(ctx, prompt_tokens, cu_lens, P, handle_out, last_logits, score, smin, smax, st);
+    const pc_status rc_mark = ctx->stage.mark(st);
+    if (rc == PC_OK) rc = rc_mark;
+    if (rc != PC_OK) {   // a HIP call failed on the way: the slots and blocks taken above go back
+        for (int p = 0; p < P; ++p) release_slot(ctx, handle_out[p]);
+        ctx->dec_seq.clear();
+        ctx->list_version++;
+    }
+    return rc;
+}
+
+static pc_status forward_chunks(pc_ctx *ctx, const int32_t *prompt_tokens, const int32_t *cu_lens, int32_t P,
+                                const int32_t *handle_out, float *last_logits, const ScoreRequest *score, int smin,
+                                int smax, hipStream_t st) {
+    const pc_model_config &m = ctx->m;
     pc_status rc = upload_slots(ctx, smin, smax, st);
     if (rc != PC_OK) return rc;
     // ---- chunks of whole prompts, at most max_batch_rows rows each
@@ -560,20 +676,21 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
             last.push_back(cu.back() - 1);
         }
         const int np = p1 - p0;
-        PC_HIP(hipMemcpyAsync(d_row_slot, row_slot.data(), (size_t)rows * 4, hipMemcpyHostToDevice, st));
-        PC_HIP(hipMemcpyAsync(d_row_pos, row_pos.data(), (size_t)rows * 4, hipMemcpyHostToDevice, st));
-        PC_HIP(hipMemcpyAsync(d_cu, cu.data(), (size_t)(np + 1) * 4, hipMemcpyHostToDevice, st));
-        PC_HIP(hipMemcpyAsync(d_pslot, pslot.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
-        PC_HIP(hipMemcpyAsync(d_last, last.data(), (size_t)np * 4, hipMemcpyHostToDevice, st));
+        if ((rc = ctx->stage.push(d_row_slot, row_slot.data(), (size_t)rows * 4, st)) != PC_OK) return rc;
+        if ((rc = ctx->stage.push(d_row_pos, row_pos.data(), (size_t)rows * 4, st)) != PC_OK) return rc;
+        if ((rc = ctx->stage.push(d_cu, cu.data(), (size_t)(np + 1) * 4, st)) != PC_OK) return rc;
+        if ((rc = ctx->stage.push(d_pslot, pslot.data(), (size_t)np * 4, st)) != PC_OK) return rc;
+        if ((rc = ctx->stage.push(d_last, last.data(), (size_t)np * 4, st)) != PC_OK) return rc;
         launch_embed(ctx->kd, ctx->tok_embed, prompt_tokens + cu_lens[p0], rows, m.d_model, m.vocab, ctx->h, st);
         const int pending = enqueue_layers(ctx, rows, d_row_slot, d_row_pos, d_cu, d_pslot, np, max_len, st);
         if (pending > 1)   // small chunk whose last projection was split: fold the slices into h first
-            launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->slices,
-                           pending, st);
+            launch_rmsnorm(ctx->kd, ctx->h, nullptr, ctx->final_norm, rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices,
+                           pending, ctx->d_sat, st);
         if (!score) {
-            launch_rmsnorm(ctx->kd, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1, st);
+            launch_rmsnorm(ctx->kd, ctx->h, d_last, ctx->final_norm, np, m.d_model, m.rms_eps, ctx->a, nullptr, 1,
+                           ctx->d_sat, st);
             launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, last_logits + (size_t)p0 * m.vocab, np, m.vocab,
-                        m.d_model, EPI_STORE_F32, nullptr, 0, st);
+                        m.d_model, EPI_STORE_F32, nullptr, 0, ctx->d_sat, st);
         } else {
             // rows whose NEXT token belongs to a completion: positions prompt_len-1 .. len-2 of every sequence
             std::vector<int32_t> local, global;
@@ -587,14 +704,14 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
             const int n_sc = (int)local.size();
             if (n_sc > 0) {
                 // the row metadata is free again once the layers are enqueued (stream order)
-                PC_HIP(hipMemcpyAsync(d_row_slot, local.data(), (size_t)n_sc * 4, hipMemcpyHostToDevice, st));
-                PC_HIP(hipMemcpyAsync(d_row_pos, global.data(), (size_t)n_sc * 4, hipMemcpyHostToDevice, st));
+                if ((rc = ctx->stage.push(d_row_slot, local.data(), (size_t)n_sc * 4, st)) != PC_OK) return rc;
+                if ((rc = ctx->stage.push(d_row_pos, global.data(), (size_t)n_sc * 4, st)) != PC_OK) return rc;
                 for (int off = 0; off < n_sc; off += ctx->score_rows) {
                     const int sr = std::min(ctx->score_rows, n_sc - off);
                     launch_rmsnorm(ctx->kd, ctx->h, d_row_slot + off, ctx->final_norm, sr, m.d_model, m.rms_eps, ctx->a,
-                                   nullptr, 1, st);
+                                   nullptr, 1, ctx->d_sat, st);
                     launch_gemm(ctx->kd, ctx->impl(), ctx->a, ctx->lm_head, ctx->score_logits, sr, m.vocab, m.d_model,
-                                EPI_STORE_F32, nullptr, 0, st);
+                                EPI_STORE_F32, nullptr, 0, ctx->d_sat, st);
                     launch_logprob(ctx->score_logits, sr, m.vocab, score->temperature, prompt_tokens, d_row_pos + off,
                                    score->out + score_done + off, st);
                 }
@@ -603,7 +720,8 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
         }
         rc = check_launch();
         if (rc != PC_OK) return rc;
-        // the metadata buffers are reused by the next chunk: pageable copies above were staged at call time
+        // the device-side metadata buffers are reused by the next chunk (stream order keeps that safe); the host
+        // side of every copy above sits in the pinned ring until the stream has passed it
         p0 = p1;
     }
     return PC_OK;
@@ -698,18 +816,27 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
             }
         }
         s.capacity = total * bs;
+        s.limit = ps.len + max_new_tokens;
         write_table_row(ctx, slot);
         seq_out[i] = slot;
         smin = std::min(smin, slot);
         smax = std::max(smax, slot);
     }
     pc_status rc = upload_slots(ctx, smin, smax, st);
-    if (rc != PC_OK) return rc;
-    if (!pairs.empty()) {
+    if (rc == PC_OK && !pairs.empty()) {
         int32_t *d_pairs = ctx->d_meta + 2 * (size_t)ctx->c.max_batch_rows + 3 * (size_t)ctx->c.max_slots + 8;
-        PC_HIP(hipMemcpyAsync(d_pairs, pairs.data(), pairs.size() * 4, hipMemcpyHostToDevice, st));
-        launch_copy_block(ctx->kd, ctx->geom(), ctx->m.n_layers, d_pairs, (int)pairs.size() / 2, st);
-        rc = check_launch();
+        rc = ctx->stage.push(d_pairs, pairs.data(), pairs.size() * 4, st);
+        if (rc == PC_OK) {
+            launch_copy_block(ctx->kd, ctx->geom(), ctx->m.n_layers, d_pairs, (int)pairs.size() / 2, st);
+            rc = check_launch();
+        }
+    }
+    const pc_status rc_mark = ctx->stage.mark(st);
+    if (rc == PC_OK) rc = rc_mark;
+    if (rc != PC_OK) {   // a HIP call failed on the way: nothing of this call is kept
+        for (int i = 0; i < n; ++i) release_slot(ctx, seq_out[i]);
+        ctx->dec_seq.clear();
+        ctx->list_version++;
     }
     return rc;
 }
@@ -746,8 +873,9 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
             PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: entry %d is not a live sequence", i);
         if (ctx->stamp[s] == gen) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d repeats", s);
         ctx->stamp[s] = gen;
-        if (ctx->slots[s].len >= ctx->slots[s].capacity)
-            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d has used its reserved tokens", s);
+        if (ctx->slots[s].len >= ctx->slots[s].limit)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d already holds its %d tokens (prompt + reserved new tokens)",
+                    s, ctx->slots[s].limit);
         max_len = std::max(max_len, ctx->slots[s].len);
     }
     if ((int)ctx->dec_seq.size() != n || memcmp(ctx->dec_seq.data(), seq, (size_t)n * 4) != 0) {
@@ -761,7 +889,12 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
             for (int k = 1; k < g; ++k)
                 if (ctx->slots[seq[i + k]].prompt != ctx->slots[seq[i]].prompt) uniform = false;
         ctx->dec_group = uniform ? g : 1;
-        PC_HIP(hipMemcpyAsync(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, hipMemcpyHostToDevice, st));
+        pc_status rc = ctx->stage.push(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, st);
+        if (rc == PC_OK) rc = ctx->stage.mark(st);
+        if (rc != PC_OK) {
+            ctx->dec_seq.clear();
+            return rc;
+        }
     }
     (void)max_len;
     if (ctx->use_graph && st != nullptr && ctx->time_class < 0) {   // the default stream cannot be captured
@@ -774,10 +907,14 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
                 ctx->exec = nullptr;
             }
             hipGraph_t graph = nullptr;
+            ctx->gkey.n = -1;   // no captured step until this one is instantiated
             PC_HIP(hipStreamBeginCapture(st, hipStreamCaptureModeThreadLocal));
             enqueue_decode(ctx, tokens_in, n, logits, st);
             hipError_t e = hipStreamEndCapture(st, &graph);
-            if (e != hipSuccess || !graph) PC_FAIL(PC_ERR_HIP, "pc_decode_step: stream capture failed: %s", hipGetErrorString(e));
+            if (e != hipSuccess || !graph) {
+                (void)hipGetLastError();
+                PC_FAIL(PC_ERR_HIP, "pc_decode_step: stream capture failed: %s", hipGetErrorString(e));
+            }
             e = hipGraphInstantiate(&ctx->exec, graph, nullptr, nullptr, 0);
             (void)hipGraphDestroy(graph);
             if (e != hipSuccess) {
@@ -815,16 +952,20 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
 }
 
 pc_status pc_sample(const float *logits, const int32_t *logit_row, int32_t n, int32_t vocab, float temperature,
-                    uint64_t seed, const uint64_t *seq_uid, const int32_t *step, int32_t step_base, int32_t eos_id,
-                    float eos_logit_bias, int32_t *tokens_out, float *logprob_out, uint8_t *finished, void *stream) {
+                    float top_p, uint64_t seed, const uint64_t *seq_uid, const int32_t *step, int32_t step_base,
+                    int32_t eos_id, float eos_logit_bias, int32_t *tokens_out, float *logprob_out, uint8_t *finished,
+                    int32_t *hist_tokens, float *hist_logprob, const int32_t *hist_index, void *stream) {
     if (n < 0 || vocab <= 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: bad count");
     if (n == 0) return PC_OK;
     if (!logits || !seq_uid || !tokens_out) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: null argument");
     if (!(temperature > 0.f)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: temperature must be positive");
+    if (!(top_p > 0.f && top_p <= 1.f)) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: top_p must lie in (0, 1]");
     if (eos_id >= vocab) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: eos_id outside the vocabulary");
     if (finished && eos_id < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: finished flags need an eos_id");
-    launch_sample(logits, logit_row, n, vocab, temperature, seed, seq_uid, step, step_base, eos_id, eos_logit_bias,
-                  tokens_out, logprob_out, finished, (hipStream_t)stream);
+    if (hist_index && !hist_tokens && !hist_logprob)
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_sample: hist_index without a history destination");
+    launch_sample(logits, logit_row, n, vocab, temperature, top_p, seed, seq_uid, step, step_base, eos_id, eos_logit_bias,
+                  tokens_out, logprob_out, finished, hist_tokens, hist_logprob, hist_index, (hipStream_t)stream);
     return check_launch();
 }
 

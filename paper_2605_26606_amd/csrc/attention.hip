@@ -41,7 +41,7 @@ __global__ __launch_bounds__(64) void attention_simt_kernel(const T *__restrict_
                                                             const int32_t *__restrict__ row_slot,
                                                             const int32_t *__restrict__ row_pos,
                                                             const int32_t *__restrict__ slot_len, int hq, KvGeom kv,
-                                                            int layer, T *__restrict__ out) {
+                                                            int layer, T *__restrict__ out, uint32_t *__restrict__ sat) {
     __shared__ float qs[256];
     __shared__ float ps[WAVE];
     const int head = blockIdx.x, r = blockIdx.y, lane = threadIdx.x;
@@ -92,24 +92,24 @@ __global__ __launch_bounds__(64) void attention_simt_kernel(const T *__restrict_
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int c = lane + WAVE * i;
-        if (c < hd) out[((int64_t)r * hq + head) * hd + c] = from_f32<T>(acc[i] * inv);
+        if (c < hd) out[((int64_t)r * hq + head) * hd + c] = from_f32_sat<T>(acc[i] * inv, sat);
     }
 }
 
 void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, const int32_t *row_pos,
                            const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
-                           hipStream_t s) {
+                           uint32_t *sat, hipStream_t s) {
     if (rows <= 0) return;
     dim3 grid(hq, rows);
     if (dtype == KD_F32)
         attention_simt_kernel<float><<<grid, 64, 0, s>>>((const float *)q, row_slot, row_pos, slot_len, hq, kv, layer,
-                                                         (float *)out);
+                                                         (float *)out, sat);
     else if (dtype == KD_BF16)
         attention_simt_kernel<bf16_t><<<grid, 64, 0, s>>>((const bf16_t *)q, row_slot, row_pos, slot_len, hq, kv,
-                                                          layer, (bf16_t *)out);
+                                                          layer, (bf16_t *)out, sat);
     else
         attention_simt_kernel<f16_t><<<grid, 64, 0, s>>>((const f16_t *)q, row_slot, row_pos, slot_len, hq, kv, layer,
-                                                         (f16_t *)out);
+                                                         (f16_t *)out, sat);
 }
 
 // =====================================================================================
@@ -269,7 +269,7 @@ __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__r
                                                                     const int32_t *__restrict__ cu_rows,
                                                                     const int32_t *__restrict__ prompt_slot, int hq,
                                                                     KvGeom kv, int layer, int n_prompts, int n_qt,
-                                                                    T *__restrict__ out) {
+                                                                    T *__restrict__ out, uint32_t *__restrict__ sat) {
     const int rep_h = hq / kv.n_kv_heads, items = (rep_h / NH) * n_qt;
     const int b = blockIdx.x, die = b % 8, j = b / 8;
     const int unit = (j / items) * 8 + die;                      // (prompt, kv head)
@@ -315,7 +315,7 @@ __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__r
                 const float inv = 1.0f / lc;
                 T *o = out + ((int64_t)(row0 + q0 + col) * hq + head0 + h) * HD;
 #pragma unroll
-                for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = from_f32<T>(st[h].o[nn][v] * inv);
+                for (int nn = 0; nn < 8; ++nn) o[16 * nn + i] = from_f32_sat<T>(st[h].o[nn][v] * inv, sat);
             }
         }
     }
@@ -323,28 +323,29 @@ __global__ __launch_bounds__(64) void attention_prefill_mfma_kernel(const T *__r
 
 template <typename T, int NH>
 static void prefill_launch(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts, int max_len,
-                           int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+                           int hq, KvGeom kv, int layer, void *out, uint32_t *sat, hipStream_t s) {
     const int n_qt = (max_len + 15) / 16, items = (hq / kv.n_kv_heads / NH) * n_qt;
     const int units = n_prompts * kv.n_kv_heads;
     const unsigned grid = (unsigned)((units + 7) / 8 * 8) * (unsigned)items;
     attention_prefill_mfma_kernel<T, NH><<<grid, 64, 0, s>>>((const T *)q, cu_rows, prompt_slot, hq, kv, layer, n_prompts,
-                                                             n_qt, (T *)out);
+                                                             n_qt, (T *)out, sat);
 }
 
 template <typename T>
 static void prefill_launch_t(const void *q, const int32_t *cu_rows, const int32_t *prompt_slot, int n_prompts,
-                             int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+                             int max_len, int hq, KvGeom kv, int layer, void *out, uint32_t *sat, hipStream_t s) {
     const int rep = hq / kv.n_kv_heads;   // heads per wave: as many as divide the group, up to three
-    if (rep % 3 == 0) prefill_launch<T, 3>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
-    else if (rep % 2 == 0) prefill_launch<T, 2>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
-    else prefill_launch<T, 1>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
+    if (rep % 3 == 0) prefill_launch<T, 3>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, sat, s);
+    else if (rep % 2 == 0) prefill_launch<T, 2>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, sat, s);
+    else prefill_launch<T, 1>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, sat, s);
 }
 
 void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
-                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s) {
+                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, uint32_t *sat,
+                                   hipStream_t s) {
     if (n_prompts <= 0 || max_len <= 0) return;
-    if (dtype == KD_BF16) prefill_launch_t<bf16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
-    else prefill_launch_t<f16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, s);
+    if (dtype == KD_BF16) prefill_launch_t<bf16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, sat, s);
+    else prefill_launch_t<f16_t>(q, cu_rows, prompt_slot, n_prompts, max_len, hq, kv, layer, out, sat, s);
 }
 
 // ---------------------------------------------------------------- decode
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(64 * NW) void attention_decode_mfma_kernel(const T 
                                                                        KvGeom kv, int layer, int rows, int n_splits,
                                                                        int group, float *__restrict__ part_ml,
                                                                        float *__restrict__ part_o,
-                                                                       T *__restrict__ out) {
+                                                                       T *__restrict__ out, uint32_t *__restrict__ sat) {
     constexpr int ROUND = 32 * NW;   // tokens one block consumes per pass of its waves
     constexpr int NSLOT = 4;         // waves that hand their output to the final sum (8 waves: pairs add up first)
     __shared__ float sm[NW][16], sl[NW][16];
@@ -484,7 +485,7 @@ __global__ __launch_bounds__(64 * NW) void attention_decode_mfma_kernel(const T 
                 const float mw = sm[w][col];
                 L += (mw == -INFINITY) ? 0.f : sl[w][col] * exp2f((mw - M) * scale_log2);
             }
-            out[((int64_t)r * hq + kvh * rep + col) * HD + c] = from_f32<T>(v / L);
+            out[((int64_t)r * hq + kvh * rep + col) * HD + c] = from_f32_sat<T>(v / L, sat);
         } else {
             const int64_t idx = ((int64_t)r * hq + kvh * rep + col) * n_splits + sp;
             part_o[idx * HD + c] = v;
@@ -514,7 +515,7 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
                                                                      int n_splits, int round,
                                                                      const float *__restrict__ part_ml,
                                                                      const float *__restrict__ part_o,
-                                                                     T *__restrict__ out) {
+                                                                     T *__restrict__ out, uint32_t *__restrict__ sat) {
     const int head = blockIdx.x, r = blockIdx.y, c = threadIdx.x;
     const int ctx = slot_len[row_slot[r]] + 1;
     const int len = split_len(ctx, n_splits, round);
@@ -529,24 +530,24 @@ __global__ __launch_bounds__(128) void attention_decode_merge_kernel(const int32
         L += f * part_ml[2 * (base + s) + 1];
         acc += f * part_o[(base + s) * HD + c];
     }
-    out[((int64_t)r * hq + head) * HD + c] = from_f32<T>(acc / L);
+    out[((int64_t)r * hq + head) * HD + c] = from_f32_sat<T>(acc / L, sat);
 }
 
 template <typename T, int NW>
 static void decode_launch_nw(const T *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
                              int layer, int n_splits, int group, float *part_ml, float *part_o, T *out, unsigned grid,
-                             hipStream_t s) {
+                             uint32_t *sat, hipStream_t s) {
     if (n_splits == 1)
         attention_decode_mfma_kernel<T, true, NW><<<grid, 64 * NW, 0, s>>>(q, row_slot, slot_len, hq, kv, layer, rows,
-                                                                           n_splits, group, part_ml, part_o, out);
+                                                                           n_splits, group, part_ml, part_o, out, sat);
     else
         attention_decode_mfma_kernel<T, false, NW><<<grid, 64 * NW, 0, s>>>(q, row_slot, slot_len, hq, kv, layer, rows,
-                                                                            n_splits, group, part_ml, part_o, out);
+                                                                            n_splits, group, part_ml, part_o, out, sat);
 }
 
 template <typename T>
 static void decode_launch(const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq, KvGeom kv,
-                          int layer, int n_splits, int group, float *scratch, void *out, hipStream_t s) {
+                          int layer, int n_splits, int group, float *scratch, void *out, uint32_t *sat, hipStream_t s) {
     float *part_ml = scratch;
     float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
     if (group < 1 || rows % group) group = 1;
@@ -554,25 +555,26 @@ static void decode_launch(const void *q, const int32_t *row_slot, const int32_t 
     const unsigned grid = (unsigned)((units + 7) / 8 * 8 * group);
     if (decode_waves(rows, kv.n_kv_heads) == 8)
         decode_launch_nw<T, 8>((const T *)q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, part_ml, part_o,
-                               (T *)out, grid, s);
+                               (T *)out, grid, sat, s);
     else
         decode_launch_nw<T, 4>((const T *)q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, part_ml, part_o,
-                               (T *)out, grid, s);
+                               (T *)out, grid, sat, s);
 }
 
 void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
                                   int hq, KvGeom kv, int layer, int n_splits, int group, float *scratch, void *out,
-                                  hipStream_t s) {
+                                  uint32_t *sat, hipStream_t s) {
     if (rows <= 0) return;
     if (dtype == KD_BF16)
-        decode_launch<bf16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, s);
+        decode_launch<bf16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, sat, s);
     else
-        decode_launch<f16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, s);
+        decode_launch<f16_t>(q, row_slot, slot_len, rows, hq, kv, layer, n_splits, group, scratch, out, sat, s);
 }
 
 // only needed when n_splits > 1
 void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                   int n_kv_heads, int n_splits, float *scratch, void *out, hipStream_t s) {
+                                   int n_kv_heads, int n_splits, float *scratch, void *out, uint32_t *sat,
+                                   hipStream_t s) {
     if (rows <= 0 || n_splits <= 1) return;
     const float *part_ml = scratch;
     const float *part_o = scratch + (size_t)rows * hq * n_splits * 2;
@@ -580,10 +582,10 @@ void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int
     dim3 mgrid(hq, rows);
     if (dtype == KD_BF16)
         attention_decode_merge_kernel<bf16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, round, part_ml,
-                                                                    part_o, (bf16_t *)out);
+                                                                    part_o, (bf16_t *)out, sat);
     else
         attention_decode_merge_kernel<f16_t><<<mgrid, 128, 0, s>>>(row_slot, slot_len, hq, n_splits, round, part_ml,
-                                                                   part_o, (f16_t *)out);
+                                                                   part_o, (f16_t *)out, sat);
 }
 
 }  // namespace pc

@@ -40,21 +40,22 @@ void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows,
 // VEC4: d % 4 == 0 and d <= 4 * 256 * RMS_MAXV: the row lives in registers between the two passes.
 static constexpr int RMS_MAXV = 6;
 
-template <typename T> __device__ inline void store4(T *p, float4 v);
-template <> __device__ inline void store4<float>(float *p, float4 v) { *(float4 *)p = v; }
-template <> __device__ inline void store4<bf16_t>(bf16_t *p, float4 v) {
+template <typename T> __device__ inline void store4(T *p, float4 v, uint32_t *sat);
+template <> __device__ inline void store4<float>(float *p, float4 v, uint32_t *) { *(float4 *)p = v; }
+template <> __device__ inline void store4<bf16_t>(bf16_t *p, float4 v, uint32_t *) {
     uint2 u = {pack2<bf16_t>(v.x, v.y), pack2<bf16_t>(v.z, v.w)};
     *(uint2 *)p = u;
 }
-template <> __device__ inline void store4<f16_t>(f16_t *p, float4 v) {
-    uint2 u = {pack2<f16_t>(v.x, v.y), pack2<f16_t>(v.z, v.w)};
+template <> __device__ inline void store4<f16_t>(f16_t *p, float4 v, uint32_t *sat) {
+    uint2 u = {pack2_sat<f16_t>(v.x, v.y, sat), pack2_sat<f16_t>(v.z, v.w, sat)};
     *(uint2 *)p = u;
 }
 
 template <typename T, bool VEC4>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, const int32_t *__restrict__ src_row,
                                                       const float *__restrict__ gain, int rows, int d, float eps,
-                                                      T *__restrict__ out, const float *__restrict__ slices, int S) {
+                                                      T *__restrict__ out, const float *__restrict__ slices, int S,
+                                                      uint32_t *__restrict__ sat) {
     __shared__ float part[4];
     const int r = blockIdx.x, tid = threadIdx.x;
     float *x = h + (int64_t)(src_row ? src_row[r] : r) * d;
@@ -110,22 +111,22 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(float *__restrict__ h, con
                 const float4 g = ((const float4 *)gain)[i];
                 float4 v = keep[j];
                 v.x = v.x * rs * g.x; v.y = v.y * rs * g.y; v.z = v.z * rs * g.z; v.w = v.w * rs * g.w;
-                store4<T>(o + 4 * i, v);
+                store4<T>(o + 4 * i, v, sat);
             }
         }
     } else {
-        for (int i = tid; i < d; i += 256) o[i] = from_f32<T>(x[i] * rs * gain[i]);
+        for (int i = tid; i < d; i += 256) o[i] = from_f32_sat<T>(x[i] * rs * gain[i], sat);
     }
 }
 
 void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *gain, int rows, int d, float eps,
-                    void *out, const float *slices, int S, hipStream_t s) {
+                    void *out, const float *slices, int S, uint32_t *sat, hipStream_t s) {
     if (rows <= 0) return;
     const bool vec = (d % 4 == 0) && d <= 4 * 256 * RMS_MAXV;
 #define PC_RMS(T)                                                                                              \
     do {                                                                                                       \
-        if (vec) rmsnorm_kernel<T, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S);  \
-        else rmsnorm_kernel<T, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S);     \
+        if (vec) rmsnorm_kernel<T, true><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S, sat);  \
+        else rmsnorm_kernel<T, false><<<rows, 256, 0, s>>>(h, src_row, gain, rows, d, eps, (T *)out, slices, S, sat);     \
     } while (0)
     if (dtype == KD_F32) PC_RMS(float);
     else if (dtype == KD_BF16) PC_RMS(bf16_t);
@@ -144,7 +145,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           const int32_t *__restrict__ slot_len,
                                                           const float *__restrict__ rope_cos,
                                                           const float *__restrict__ rope_sin, int hq, KvGeom kv,
-                                                          int layer, T *__restrict__ q_out) {
+                                                          int layer, T *__restrict__ q_out,
+                                                          uint32_t *__restrict__ sat) {
     const int r = blockIdx.x;
     const int hd = kv.head_dim, half = hd / 2, hkv = kv.n_kv_heads, bs = kv.block_size;
     const int nq = hq * half, nk = hkv * half, nv = hkv * hd;
@@ -165,8 +167,8 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
         const float x1 = val(head * hd + j), x2 = val(head * hd + j + half);
         const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
         T *qd = q_out + (int64_t)r * hq * hd + head * hd;
-        qd[j] = from_f32<T>(x1 * c - x2 * sgn);
-        qd[j + half] = from_f32<T>(x2 * c + x1 * sgn);
+        qd[j] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
+        qd[j + half] = from_f32_sat<T>(x2 * c + x1 * sgn, sat);
         return;
     }
     const int blk = kv.block_table[(int64_t)slot * kv.max_blocks_per_slot + pos / bs];
@@ -178,31 +180,31 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
         const float x1 = val(koff + head * hd + j), x2 = val(koff + head * hd + j + half);
         const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
         T *kd = pool + (int64_t)head * kv.head_elems() + (int64_t)tin * hd;
-        kd[j] = from_f32<T>(x1 * c - x2 * sgn);
-        kd[j + half] = from_f32<T>(x2 * c + x1 * sgn);
+        kd[j] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
+        kd[j + half] = from_f32_sat<T>(x2 * c + x1 * sgn, sat);
     } else {                // v heads -> V^T [hd][tok]
         const int i = item - nq - nk, head = i / hd, j = i % hd;
         const int voff = (hq + hkv) * hd;
         T *vd = pool + (int64_t)head * kv.head_elems() + (int64_t)bs * hd;
-        vd[(int64_t)j * bs + tin] = from_f32<T>(val(voff + head * hd + j));
+        vd[(int64_t)j * bs + tin] = from_f32_sat<T>(val(voff + head * hd + j), sat);
     }
 }
 
 void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
-                        KvGeom kv, int layer, void *q_out, hipStream_t s) {
+                        KvGeom kv, int layer, void *q_out, uint32_t *sat, hipStream_t s) {
     if (rows <= 0) return;
     const int items = hq * (kv.head_dim / 2) + kv.n_kv_heads * (kv.head_dim / 2) + kv.n_kv_heads * kv.head_dim;
     const dim3 grid(rows, (items + 255) / 256);
     if (dtype == KD_F32)
         rope_append_kernel<float><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                       layer, (float *)q_out);
+                                                       layer, (float *)q_out, sat);
     else if (dtype == KD_BF16)
         rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                        layer, (bf16_t *)q_out);
+                                                        layer, (bf16_t *)q_out, sat);
     else
         rope_append_kernel<f16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                       layer, (f16_t *)q_out);
+                                                       layer, (f16_t *)q_out, sat);
 }
 
 // ------------------------------------------------------------------ bookkeeping

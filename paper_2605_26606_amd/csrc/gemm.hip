@@ -14,14 +14,15 @@ namespace pc {
 
 __device__ inline float silu_f(float x) { return x / (1.0f + expf(-x)); }
 
-template <typename T> __device__ inline void store_out(T *p, float v) { *p = from_f32<T>(v); }
+template <typename T> __device__ inline void store_out(T *p, float v, uint32_t *sat) { *p = from_f32_sat<T>(v, sat); }
 
 // =====================================================================================
 // plain-ALU GEMM: 64x64 tile, BK = 16, 256 threads, 4x4 outputs per thread at stride 16
 // =====================================================================================
 template <typename T, int EPI>
 __global__ __launch_bounds__(256) void gemm_simt_kernel(const T *__restrict__ A, const T *__restrict__ W,
-                                                        void *__restrict__ Cv, int M, int N, int K) {
+                                                        void *__restrict__ Cv, int M, int N, int K,
+                                                        uint32_t *__restrict__ sat) {
     constexpr int BM = 64, BN = 64, BK = 16;
     __shared__ float As[BK][BM + 4];
     __shared__ float Ws[BK][BN + 4];
@@ -64,7 +65,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const T *__restrict__ A,
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if (n0 + tx + 16 * j + 32 < N)
-                    store_out(&C[(int64_t)row * (N / 2) + ob + tx + 16 * j], silu_f(acc[i][j]) * acc[i][j + 2]);
+                    store_out(&C[(int64_t)row * (N / 2) + ob + tx + 16 * j], silu_f(acc[i][j]) * acc[i][j + 2], sat);
             }
         } else {
 #pragma unroll
@@ -73,21 +74,21 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(const T *__restrict__ A,
                 if (col >= N) continue;
                 if (EPI == EPI_STORE_F32) ((float *)Cv)[(int64_t)row * N + col] = acc[i][j];
                 if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][j];
-                if (EPI == EPI_STORE_T) store_out(&((T *)Cv)[(int64_t)row * N + col], acc[i][j]);
+                if (EPI == EPI_STORE_T) store_out(&((T *)Cv)[(int64_t)row * N + col], acc[i][j], sat);
             }
         }
     }
 }
 
 template <typename T>
-static void gemm_simt(const void *A, const void *W, void *C, int M, int N, int K, int epi, hipStream_t s) {
+static void gemm_simt(const void *A, const void *W, void *C, int M, int N, int K, int epi, uint32_t *sat, hipStream_t s) {
     dim3 grid((N + 63) / 64, (M + 63) / 64);
     const T *a = (const T *)A, *w = (const T *)W;
     switch (epi) {
-        case EPI_STORE_F32: gemm_simt_kernel<T, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, C, M, N, K); break;
-        case EPI_RESID_F32: gemm_simt_kernel<T, EPI_RESID_F32><<<grid, 256, 0, s>>>(a, w, C, M, N, K); break;
-        case EPI_SWIGLU: gemm_simt_kernel<T, EPI_SWIGLU><<<grid, 256, 0, s>>>(a, w, C, M, N, K); break;
-        default: gemm_simt_kernel<T, EPI_STORE_T><<<grid, 256, 0, s>>>(a, w, C, M, N, K); break;
+        case EPI_STORE_F32: gemm_simt_kernel<T, EPI_STORE_F32><<<grid, 256, 0, s>>>(a, w, C, M, N, K, sat); break;
+        case EPI_RESID_F32: gemm_simt_kernel<T, EPI_RESID_F32><<<grid, 256, 0, s>>>(a, w, C, M, N, K, sat); break;
+        case EPI_SWIGLU: gemm_simt_kernel<T, EPI_SWIGLU><<<grid, 256, 0, s>>>(a, w, C, M, N, K, sat); break;
+        default: gemm_simt_kernel<T, EPI_STORE_T><<<grid, 256, 0, s>>>(a, w, C, M, N, K, sat); break;
     }
 }
 
@@ -127,7 +128,7 @@ template <int N> __device__ inline void wait_vmcnt_le() {
 template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK, int EPI, bool M16 = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                         void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
-                                                        int S, int plain) {
+                                                        int S, int plain, uint32_t *__restrict__ sat) {
     constexpr int CPR = BK / 8;                           // 16-byte chunks per tile row
     constexpr int RPL = 64 / CPR;                         // tile rows one wave-wide load covers
     // rows that share a swizzle value (measured with a read-rate probe: 16-row fragment reads of 64-byte
@@ -317,7 +318,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                                 const int row = rbase + v;
                                 if (row < M)
                                     C[(int64_t)row * (N / 2) + ocol] =
-                                        from_f32<T>(silu_f(acc[i][4 * p2 + q][v]) * acc[i][4 * p2 + 2 + q][v]);
+                                        from_f32_sat<T>(silu_f(acc[i][4 * p2 + q][v]) * acc[i][4 * p2 + 2 + q][v], sat);
                             }
                         }
                     }
@@ -332,7 +333,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                         if (row >= M) continue;
                         if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
                         if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
-                        if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(acc[i][jj][v]);
+                        if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32_sat<T>(acc[i][jj][v], sat);
                     }
                 }
             }
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                         int row = rbase + 8 * (v / 4) + (v % 4);
                         if (row < M)
                             C[(int64_t)row * (N / 2) + ocol] =
-                                from_f32<T>(silu_f(acc[i][2 * p2][v]) * acc[i][2 * p2 + 1][v]);
+                                from_f32_sat<T>(silu_f(acc[i][2 * p2][v]) * acc[i][2 * p2 + 1][v], sat);
                     }
                 }
             }
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                     if (row >= M) continue;
                     if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
                     if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
-                    if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32<T>(acc[i][jj][v]);
+                    if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32_sat<T>(acc[i][jj][v], sat);
                 }
             }
         }
@@ -392,20 +393,20 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64, b
         if constexpr (swiglu_ok) set_attr<EPI_SWIGLU>();
     }
     // split > 1 only with EPI_STORE_F32, C then being the slice buffer [split][M][N]
-    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, int split, hipStream_t s) {
+    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, int split, uint32_t *sat, hipStream_t s) {
         const int mb = (M + BM - 1) / BM, nb = (N + BN - 1) / BN;
         const int units = nb * split;
         const int plain = (split == 1 && mb > 4) ? 1 : 0;
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain, sat); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat); break;
             case EPI_SWIGLU:
                 if constexpr (swiglu_ok)
-                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain);
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat);
                 break;
-            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain); break;
+            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat); break;
         }
     }
     // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
@@ -440,27 +441,27 @@ void gemm_init() {
 
 template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
-                              size_t slice_cap_floats, hipStream_t s);
+                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s);
 
 int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                float *slices, size_t slice_cap_floats, hipStream_t s) {
+                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s) {
     if (M <= 0 || N <= 0) return 1;
     if (dtype == KD_F32) {
-        gemm_simt<float>(A, W, C, M, N, K, epi, s);
+        gemm_simt<float>(A, W, C, M, N, K, epi, sat, s);
         return 1;
     }
     if (impl == 0 || (K % 64) != 0) {
-        if (dtype == KD_BF16) gemm_simt<bf16_t>(A, W, C, M, N, K, epi, s);
-        else gemm_simt<f16_t>(A, W, C, M, N, K, epi, s);
+        if (dtype == KD_BF16) gemm_simt<bf16_t>(A, W, C, M, N, K, epi, sat, s);
+        else gemm_simt<f16_t>(A, W, C, M, N, K, epi, sat, s);
         return 1;
     }
-    if (dtype == KD_BF16) return gemm_mfma_dispatch<bf16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, s);
-    return gemm_mfma_dispatch<f16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, s);
+    if (dtype == KD_BF16) return gemm_mfma_dispatch<bf16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s);
+    return gemm_mfma_dispatch<f16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s);
 }
 
 template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
-                              size_t slice_cap_floats, hipStream_t s) {
+                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s) {
     // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
     typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
     // prefill: 16x16x32 products (measured +3 to +12 % over 32x32x16 at 16384 rows, nothing at decode sizes;
@@ -477,44 +478,44 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
         // 256x256 tiles where they still come in several rounds per CU (the wide projections: +10 % measured);
         // the narrow ones (1536 columns: 1.5 rounds of such tiles) keep 256x128
         const int64_t wide_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-        if (wide_tiles >= 2 * 256) CfgWide::run(A, W, C, M, N, K, epi, 1, s);
-        else CfgPrefill::run(A, W, C, M, N, K, epi, 1, s);
+        if (wide_tiles >= 2 * 256) CfgWide::run(A, W, C, M, N, K, epi, 1, sat, s);
+        else CfgPrefill::run(A, W, C, M, N, K, epi, 1, sat, s);
         return 1;
     }
     // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
     const int nb128 = (N + 127) / 128;
     if (epi == EPI_SWIGLU || nb128 >= 96) {   // wide outputs: no K slices needed
-        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, s);               // four 128-row blocks, three per CU at a time
-        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, s);          // three 128-row blocks, not two of 256
-        else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, s);   // a weight tile is fetched by exactly one block
-        else CfgLarge::run(A, W, C, M, N, K, epi, 1, s);
+        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, sat, s);               // four 128-row blocks, three per CU at a time
+        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, sat, s);          // three 128-row blocks, not two of 256
+        else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, sat, s);   // a weight tile is fetched by exactly one block
+        else CfgLarge::run(A, W, C, M, N, K, epi, 1, sat, s);
         return 1;
     }
     if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the feed-forward down projection)
         if (M > 256) {
             const int split = can_split ? CfgMidTall::pick_split(M, N, K, slice_cap_floats, 240) : 1;
             if (split > 1) {
-                CfgMidTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+                CfgMidTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
                 return split;
             }
-            CfgMidTall::run(A, W, C, M, N, K, epi, 1, s);
+            CfgMidTall::run(A, W, C, M, N, K, epi, 1, sat, s);
             return 1;
         }
         const int split = can_split ? CfgMid::pick_split(M, N, K, slice_cap_floats, 240) : 1;
         if (split > 1) {
-            CfgMid::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+            CfgMid::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
             return split;
         }
-        CfgMid::run(A, W, C, M, N, K, epi, 1, s);
+        CfgMid::run(A, W, C, M, N, K, epi, 1, sat, s);
         return 1;
     }
     const int split = can_split ? CfgSmall::pick_split(M, N, K, slice_cap_floats, 192) : 1;
     if (split > 1) {
-        CfgSmall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, s);
+        CfgSmall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
         return split;
     }
-    CfgSmall::run(A, W, C, M, N, K, epi, 1, s);
+    CfgSmall::run(A, W, C, M, N, K, epi, 1, sat, s);
     return 1;
 }
 

@@ -88,8 +88,8 @@ static int bench_attention(int n, int group, int lp, int gen, int bs, bool group
     for (int g : {group, 1}) {
         if (grouped_only && g != group) continue;
         auto layer = [&](int l) {   // the merge pass only runs when the context is split
-            launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, 0);
-            launch_attention_decode_merge(KD_F16, d_slot, d_len, n, hq, hkv, splits, scratch, out, 0);
+            launch_attention_decode_mfma(KD_F16, q, d_slot, d_len, n, hq, kv, l, splits, g, scratch, out, nullptr, 0);
+            launch_attention_decode_merge(KD_F16, d_slot, d_len, n, hq, hkv, splits, scratch, out, nullptr, 0);
         };
         for (int l = 0; l < L; ++l) layer(l);
         CK(hipDeviceSynchronize());
@@ -150,11 +150,11 @@ static int run_gemm(const char *name, int M, int N, int K, int epi, int split, s
     CK(hipEventCreate(&e0));
     CK(hipEventCreate(&e1));
     const int ring = (int)Ws.size();
-    for (int i = 0; i < 3; ++i) Cfg::run(A, Ws[i % ring], split > 1 ? (void *)slices : C, M, N, K, epi, split, 0);
+    for (int i = 0; i < 3; ++i) Cfg::run(A, Ws[i % ring], split > 1 ? (void *)slices : C, M, N, K, epi, split, nullptr, 0);
     CK(hipDeviceSynchronize());
     const int iters = 24;
     CK(hipEventRecord(e0, 0));
-    for (int i = 0; i < iters; ++i) Cfg::run(A, Ws[i % ring], split > 1 ? (void *)slices : C, M, N, K, epi, split, 0);
+    for (int i = 0; i < iters; ++i) Cfg::run(A, Ws[i % ring], split > 1 ? (void *)slices : C, M, N, K, epi, split, nullptr, 0);
     CK(hipEventRecord(e1, 0));
     CK(hipEventSynchronize(e1));
     float ms;

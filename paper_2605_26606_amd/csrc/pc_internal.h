@@ -53,6 +53,16 @@ template <> __device__ inline f16_t from_f32<f16_t>(float f) { return f32_to_f16
 template <typename T> __device__ inline uint32_t pack2(float a, float b) {
     return (uint32_t)from_f32<T>(a).x | ((uint32_t)from_f32<T>(b).x << 16);
 }
+// Stores of activations and cache entries: a value that leaves the half range is clamped (f32_to_f16)
+// and counted in *sat, so that a caller can tell that its model does not fit IEEE-half activations.
+template <typename T> __device__ inline T from_f32_sat(float f, uint32_t *sat) { return from_f32<T>(f); }
+template <> __device__ inline f16_t from_f32_sat<f16_t>(float f, uint32_t *sat) {
+    if (sat && fabsf(f) > 65504.f) atomicAdd(sat, 1u);
+    return f32_to_f16(f);
+}
+template <typename T> __device__ inline uint32_t pack2_sat(float a, float b, uint32_t *sat) {
+    return (uint32_t)from_f32_sat<T>(a, sat).x | ((uint32_t)from_f32_sat<T>(b, sat).x << 16);
+}
 
 // Kernel data types: the type of activations, KV cache and the library's weight copies.
 //   KD_F32   fp32 models
@@ -138,46 +148,50 @@ void launch_embed(int dtype, const void *table, const int32_t *tokens, int rows,
 // [S][rows][d] pending (a split-K product not yet added to the residual stream), h[r] += their sum first
 // (written back); src_row must be NULL then.
 void launch_rmsnorm(int dtype, float *h, const int32_t *src_row, const float *gain, int rows, int d, float eps,
-                    void *out, const float *slices, int S, hipStream_t s);
+                    void *out, const float *slices, int S, uint32_t *sat, hipStream_t s);
 // C = A[M,K] * W[N,K]^T with the given epilogue.  impl 0: plain ALU, 1: matrix cores (bf16 only)
 void gemm_init();   // once per process: raises the dynamic-LDS limit of the matrix-core kernels
 // Returns the number of K slices S the product was cut into.  S == 1: C holds the finished result.
 // S > 1 (only when `slices` is given, for EPI_STORE_F32 / EPI_RESID_F32 at decode sizes): C is untouched
 // and `slices` holds S fp32 partial products [S][M][N]; the consumer adds them in slice order (and, for
 // EPI_RESID_F32, adds that sum to the residual stream).
+// `sat`: counter of half-range clamps of the epilogues that store activations (may be NULL).
 int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                float *slices, size_t slice_cap_floats, hipStream_t s);
+                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s);
 // Rotates q and k at each row's position, writes q (model dtype) and appends k, v to the cache.
 //   qkv fp32 [S][rows, (hq+2hkv)*hd] (S >= 1 K slices, summed here); row_slot [rows];
 //   row_pos [rows] or NULL (then pos = slot_len[slot])
 void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
-                        KvGeom kv, int layer, void *q_out, hipStream_t s);
+                        KvGeom kv, int layer, void *q_out, uint32_t *sat, hipStream_t s);
 // Attention of each row's query heads over its slot's cache, positions 0..pos (plain ALU).
 void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, const int32_t *row_pos,
                            const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
-                           hipStream_t s);
+                           uint32_t *sat, hipStream_t s);
 // Matrix-core attention (bf16).  Prefill: rows of each prompt are contiguous and start at position 0.
 void launch_attention_prefill_mfma(int dtype, const void *q, const int32_t *cu_rows, const int32_t *prompt_slot,
-                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, hipStream_t s);
+                                   int n_prompts, int max_len, int hq, KvGeom kv, int layer, void *out, uint32_t *sat,
+                                   hipStream_t s);
 // Decode: one query row per sequence.  n_splits = attention_decode_splits(...): with one split the
 // kernel writes `out` itself, otherwise it leaves partial results in `scratch` for the merge pass.
 int attention_decode_splits(int rows, int n_kv_heads, int max_ctx);
 // `group`: consecutive rows that share a prompt (1 if unknown): they are scheduled on one die.
 void launch_attention_decode_mfma(int dtype, const void *q, const int32_t *row_slot, const int32_t *slot_len, int rows,
                                   int hq, KvGeom kv, int layer, int n_splits, int group, float *scratch, void *out,
-                                  hipStream_t s);
+                                  uint32_t *sat, hipStream_t s);
 void launch_attention_decode_merge(int dtype, const int32_t *row_slot, const int32_t *slot_len, int rows, int hq,
-                                   int n_kv_heads, int n_splits, float *scratch, void *out, hipStream_t s);
+                                   int n_kv_heads, int n_splits, float *scratch, void *out, uint32_t *sat,
+                                   hipStream_t s);
 size_t attention_decode_scratch_floats(int max_rows, int hq, int hd);
 
 void launch_advance_len(int32_t *slot_len, const int32_t *row_slot, int rows, hipStream_t s);
 void launch_copy_block(int dtype, KvGeom kv, int n_layers, const int32_t *src_dst_pairs, int n_pairs, hipStream_t s);
 void launch_fill_i32(int32_t *p, int32_t v, int64_t n, hipStream_t s);
 
-void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, uint64_t seed,
-                   const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
-                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, hipStream_t s);
+void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, float top_p,
+                   uint64_t seed, const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
+                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, int32_t *hist_tokens,
+                   float *hist_logprob, const int32_t *hist_index, hipStream_t s);
 // out[r] = log softmax(logits[r] / T)[tokens[token_index[r] + 1]]
 void launch_logprob(const float *logits, int n, int vocab, float temperature, const int32_t *tokens,
                     const int32_t *token_index, float *out, hipStream_t s);

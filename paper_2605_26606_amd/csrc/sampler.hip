@@ -68,7 +68,8 @@ template <int VEC>
 __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
     const float *__restrict__ logits, const int32_t *__restrict__ logit_row, int vocab, float inv_t, uint64_t seed,
     const uint64_t *__restrict__ seq_uid, const int32_t *__restrict__ step, int step_base, int eos_id, float eos_bias,
-    int32_t *__restrict__ tokens_out, float *__restrict__ logprob_out, uint8_t *__restrict__ finished) {
+    int32_t *__restrict__ tokens_out, float *__restrict__ logprob_out, uint8_t *__restrict__ finished,
+    int32_t *__restrict__ hist_tokens, float *__restrict__ hist_logprob, const int32_t *__restrict__ hist_index) {
     __shared__ float s_wm[SAMPLE_WAVES];
     __shared__ double s_ws[SAMPLE_WAVES];
     __shared__ double s_sub[SAMPLE_WAVES];
@@ -78,6 +79,9 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
         if (tid == 0) {
             tokens_out[row] = eos_id;
             if (logprob_out) logprob_out[row] = 0.f;
+            const int hi = hist_index ? hist_index[row] : row;
+            if (hist_tokens) hist_tokens[hi] = eos_id;
+            if (hist_logprob) hist_logprob[hi] = 0.f;
         }
         return;
     }
@@ -259,25 +263,30 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
     }
     if (lane == 0) {
         tokens_out[row] = token;
-        if (logprob_out) logprob_out[row] = (float)((double)tok_x - (double)M - log(Z));
+        const float lp = (float)((double)tok_x - (double)M - log(Z));
+        if (logprob_out) logprob_out[row] = lp;
         if (finished && token == eos_id) finished[row] = 1;
+        const int hi = hist_index ? hist_index[row] : row;
+        if (hist_tokens) hist_tokens[hi] = token;
+        if (hist_logprob) hist_logprob[hi] = lp;
     }
 }
 
-void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, uint64_t seed,
-                   const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
-                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, hipStream_t s) {
+void launch_sample(const float *logits, const int32_t *logit_row, int n, int vocab, float temperature, float top_p,
+                   uint64_t seed, const uint64_t *seq_uid, const int32_t *step, int step_base, int eos_id, float eos_bias,
+                   int32_t *tokens_out, float *logprob_out, uint8_t *finished, int32_t *hist_tokens,
+                   float *hist_logprob, const int32_t *hist_index, hipStream_t s) {
     if (n <= 0) return;
     const float inv_t = 1.0f / temperature;
     const bool vec = (vocab % 4 == 0) && (((uintptr_t)logits) % 16 == 0);
     if (vec)
         sample_kernel<4><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
                                                            step_base, eos_id, eos_bias, tokens_out, logprob_out,
-                                                           finished);
+                                                           finished, hist_tokens, hist_logprob, hist_index);
     else
         sample_kernel<1><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
                                                            step_base, eos_id, eos_bias, tokens_out, logprob_out,
-                                                           finished);
+                                                           finished, hist_tokens, hist_logprob, hist_index);
 }
 
 // log softmax(logits / T) at a given token per row (teacher-forced scoring: Section 3.1, the per-token

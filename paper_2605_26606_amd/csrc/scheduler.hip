@@ -57,6 +57,22 @@ pc_status pc_sched_pilot(pc_sched *s, const int64_t *prompt_uid, const int64_t *
     }
     int32_t kept = 0, ev = 0, easy = 0, hard = 0;
     const float lo = s->cfg.p_lower, hi = s->cfg.p_upper, solve = s->cfg.p_solve;
+    // Growing the containers can run out of host memory.  Nothing may leave through the C boundary as an
+    // exception, and a failed call leaves the state as it was: what was appended is taken back.
+    const size_t buffer_before = s->buffer.size();
+    std::vector<int64_t> newly_evicted;
+    try {
+        for (int32_t q = 0; q < n; ++q) {
+            const float p = p_hat[q];
+            if (p >= lo && p <= hi) s->buffer.push_back({prompt_uid[q], tag ? tag[q] : 0, s->t});
+            if (p >= solve && s->evicted.insert(prompt_uid[q]).second) newly_evicted.push_back(prompt_uid[q]);
+        }
+    } catch (...) {
+        s->buffer.resize(buffer_before);
+        for (int64_t u : newly_evicted) s->evicted.erase(u);
+        set_error("pc_sched_pilot: out of host memory");
+        return PC_ERR_OOM;
+    }
     for (int32_t q = 0; q < n; ++q) {
         const float p = p_hat[q];
         uint8_t c;
@@ -69,13 +85,9 @@ pc_status pc_sched_pilot(pc_sched *s, const int64_t *prompt_uid, const int64_t *
         } else {
             c = 1;
             ++kept;
-            s->buffer.push_back({prompt_uid[q], tag ? tag[q] : 0, s->t});
         }
         const bool e = p >= solve;
-        if (e) {
-            ++ev;
-            s->evicted.insert(prompt_uid[q]);
-        }
+        ev += e;
         if (cls) cls[q] = c;
         if (evict) evict[q] = e ? 1 : 0;
     }
@@ -116,6 +128,18 @@ pc_status pc_sched_commit(pc_sched *s, int64_t *uid_out, int64_t *tag_out, int32
         set_error("pc_sched_commit: %zu entries age out, aged_cap is %d", aged, aged_cap);
         return PC_ERR_INVALID_ARG;
     }
+    // the entries that stay, built first: this is the only step that can run out of memory, and nothing has
+    // been written or changed yet
+    std::deque<pc_sched::Entry> rest;
+    try {
+        for (size_t i = n_old; i < first_cur; ++i)
+            if (!too_old(s->buffer[i])) rest.push_back(s->buffer[i]);
+        for (size_t i = first_cur + n_cur; i < nb; ++i)
+            if (!too_old(s->buffer[i])) rest.push_back(s->buffer[i]);
+    } catch (...) {
+        set_error("pc_sched_commit: out of host memory");
+        return PC_ERR_OOM;
+    }
     size_t k = 0;
     auto emit = [&](const pc_sched::Entry &e) {
         uid_out[k] = e.uid;
@@ -125,19 +149,15 @@ pc_status pc_sched_commit(pc_sched *s, int64_t *uid_out, int64_t *tag_out, int32
     };
     for (size_t i = 0; i < n_cur; ++i) emit(s->buffer[first_cur + i]);
     for (size_t i = 0; i < n_old; ++i) emit(s->buffer[i]);
-    std::deque<pc_sched::Entry> rest;
     size_t a = 0;
-    auto keep_or_drop = [&](const pc_sched::Entry &e) {
-        if (too_old(e)) {
-            if (aged_uid_out) aged_uid_out[a] = e.uid;
-            if (aged_tag_out) aged_tag_out[a] = e.tag;
-            ++a;
-        } else {
-            rest.push_back(e);
-        }
+    auto report_aged = [&](const pc_sched::Entry &e) {
+        if (!too_old(e)) return;
+        if (aged_uid_out) aged_uid_out[a] = e.uid;
+        if (aged_tag_out) aged_tag_out[a] = e.tag;
+        ++a;
     };
-    for (size_t i = n_old; i < first_cur; ++i) keep_or_drop(s->buffer[i]);
-    for (size_t i = first_cur + n_cur; i < nb; ++i) keep_or_drop(s->buffer[i]);
+    for (size_t i = n_old; i < first_cur; ++i) report_aged(s->buffer[i]);
+    for (size_t i = first_cur + n_cur; i < nb; ++i) report_aged(s->buffer[i]);
     s->buffer.swap(rest);
     *n_selected = (int32_t)k;
     if (n_aged) *n_aged = (int32_t)a;

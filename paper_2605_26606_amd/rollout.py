@@ -8,7 +8,7 @@ here with elementwise tensor ops, as a caller would apply its own verifier.
 """
 from __future__ import annotations
 
-from typing import Optional
+from typing import Optional, Sequence
 
 import numpy as np
 import torch
@@ -26,7 +26,8 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
              seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
              eos_logit_bias: float = 0.0, stream=None, keep_logits_rows: Optional[np.ndarray] = None,
              poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None,
-             compact: bool = True, keep_logprobs: bool = False):
+             compact: bool = True, keep_logprobs: bool = False, top_p: float = 1.0,
+             keep_logits_steps: Optional[Sequence[int]] = None):
     """Samples one completion per entry of `handles` (prompt handles, one per
     sequence).  Token 0 comes from the prompt's prefill logits
     (first_logits[logit_rows[i]]); tokens 1.. from decode steps.
@@ -43,8 +44,9 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
     Returns dict(tokens [n, T] int32 device (eos_id-padded after the end when
     EOS is on), lengths [n] int32 device, steps_run, rows_decoded (sum of the
     batch sizes of the decode steps), logits / logits_rows (optional: per step
-    the logits of the requested rows that were still in the batch, and which
-    rows those are; for parity tests))."""
+    -- or only for the steps in keep_logits_steps, then with logits_steps naming
+    them -- the logits of the requested rows that were still in the batch, and
+    which rows those are; for parity tests))."""
     dev = first_logits.device
     n = len(handles)
     V = ctx.vocab
@@ -65,17 +67,18 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
     if keep is not None:
         keep_mask = torch.zeros(n, dtype=torch.bool, device=dev)
         keep_mask[keep] = True
-    active = None                      # original index of each batch row; None = identity
+    active = None                      # original index of each batch row (int32, device); None = identity
     lp_hist = torch.zeros((T, n), dtype=torch.float32, device=dev) if keep_logprobs else None
-    lp = torch.zeros(n, dtype=torch.float32, device=dev) if keep_logprobs else None
-    B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, lp,
-                finished, stream)
-    hist[0, :n].copy_(cur)
-    if keep_logprobs:
-        lp_hist[0].copy_(lp)
-    if keep is not None:
+    # the sampler itself files every token (and its log-probability) under [step][original index]: no copy
+    # kernel per step, also after the batch has shrunk
+    B.pc_sample(first_logits, rows_d, n, V, temperature, seed, uid_d, None, 0, eos_id, eos_logit_bias, cur, None,
+                finished, stream, top_p=top_p, hist_tokens=hist[0], hist_logprob=None if lp_hist is None else lp_hist[0])
+    keep_steps = None if keep_logits_steps is None else set(int(x) for x in keep_logits_steps)
+    out["logits_steps"] = []
+    if keep is not None and (keep_steps is None or 0 in keep_steps):
         out["logits"].append(first_logits[rows_d.long()[keep]].clone())
         out["logits_rows"].append(keep.clone())
+        out["logits_steps"].append(0)
     steps, rows_decoded = 1, 0
     for t in range(1, T):
         if finished is not None and t % poll_every == 0:
@@ -87,13 +90,11 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
                 B.pc_release(ctx, seqs[fin], 0)
                 seqs = np.ascontiguousarray(seqs[alive])
                 alive_d = torch.from_numpy(alive).to(dev)
-                active = alive_d if active is None else active[alive_d]
+                active = alive_d.to(torch.int32) if active is None else active[alive_d].contiguous()
                 cur = cur[alive_d].contiguous()
                 uid_d = uid_d[alive_d].contiguous()
                 finished = finished[alive_d].contiguous()
                 logits = logits[:len(alive)]
-                if keep_logprobs:
-                    lp = lp[:len(alive)]
         m = len(seqs)
         if time_every > 0 and t % time_every == time_every // 2:
             # this step runs eagerly with HIP events around every launch of one kernel class
@@ -102,24 +103,19 @@ def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_
                 timed_steps.append((t, m))
         B.pc_decode_step(ctx, seqs, cur, logits, stream)
         rows_decoded += m
-        if keep is not None:
+        if keep is not None and (keep_steps is None or t in keep_steps):
+            out["logits_steps"].append(t)
             if active is None:
                 out["logits"].append(logits[keep].clone())
                 out["logits_rows"].append(keep.clone())
             else:
-                sel = keep_mask[active]
+                act_l = active.long()
+                sel = keep_mask[act_l]
                 out["logits"].append(logits[sel].clone())
-                out["logits_rows"].append(active[sel].clone())
-        B.pc_sample(logits, None, m, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, lp,
-                    finished, stream)
-        if active is None:
-            hist[t, :n].copy_(cur)
-            if keep_logprobs:
-                lp_hist[t].copy_(lp)
-        else:
-            hist[t].index_copy_(0, active, cur)
-            if keep_logprobs:
-                lp_hist[t].index_copy_(0, active, lp)
+                out["logits_rows"].append(act_l[sel].clone())
+        B.pc_sample(logits, None, m, V, temperature, seed, uid_d, None, t, eos_id, eos_logit_bias, cur, None,
+                    finished, stream, top_p=top_p, hist_tokens=hist[t],
+                    hist_logprob=None if lp_hist is None else lp_hist[t], hist_index=active)
         steps += 1
     B.pc_release(ctx, seqs, 0)
     toks = hist[:, :n].t().contiguous()

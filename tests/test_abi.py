@@ -44,9 +44,15 @@ def test_host_side_argument_checks_need_no_gpu():
     one = np.zeros(4, np.int32)
     assert lib.pc_select_commit(one.ctypes.data, 4, 0.8, 0.75, 1.0, 0, None, None, one.ctypes.data, None,
                                 one.ctypes.data, None) == -1      # p_lower > p_upper
-    assert lib.pc_sample(None, None, 1, 16, 1.0, 0, None, None, 0, -1, 0.0, None, None, None, None) == -1
-    assert lib.pc_sample(one.ctypes.data, None, 1, 16, 0.0, 0, one.ctypes.data, None, 0, -1, 0.0, one.ctypes.data,
-                         None, None, None) == -1                   # temperature must be positive
+    assert lib.pc_sample(None, None, 1, 16, 1.0, 1.0, 0, None, None, 0, -1, 0.0, None, None, None, None, None, None,
+                         None) == -1
+    assert lib.pc_sample(one.ctypes.data, None, 1, 16, 0.0, 1.0, 0, one.ctypes.data, None, 0, -1, 0.0,
+                         one.ctypes.data, None, None, None, None, None, None) == -1   # temperature must be positive
+    for bad_top_p in (0.0, 1.5, float("nan")):
+        assert lib.pc_sample(one.ctypes.data, None, 1, 16, 1.0, bad_top_p, 0, one.ctypes.data, None, 0, -1, 0.0,
+                             one.ctypes.data, None, None, None, None, None, None) == -1
+        assert b"top_p" in lib.pc_last_error()
+    assert lib.pc_saturation_count(None, None, 0) == -1
     assert lib.pc_create(None, None, None, None) == -1
     assert lib.pc_decode_step(None, None, None, 0, None, None) == -1
     assert lib.pc_destroy(None) == 0

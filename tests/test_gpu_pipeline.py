@@ -50,6 +50,22 @@ def _check_allocation(wl, got):
     assert got["tokens_generated"] == int(got["pilot_lens"].sum() + got["commit_lens"].sum())
 
 
+def _teacher_forced_agreement(wl, w, prompts, uids, tokens, rollout_indices, seed):
+    """tokens [n_prompts, len(rollout_indices), T] from the GPU; the oracle recomputes the logits of every
+    position from the GPU's own history (brute force) and samples with the same uniform.
+    -> (positions on which the oracle picks the GPU's token, positions)"""
+    ok = tot = 0
+    for q in range(len(prompts)):
+        for a, j in enumerate(rollout_indices):
+            seq = np.concatenate([prompts[q], tokens[q, a]])
+            lg = decoder.forward_full(wl.model, w, seq[:-1], rows=np.arange(len(prompts[q]) - 1, len(seq) - 1))
+            for t in range(tokens.shape[2]):
+                u = philox.sampling_uniform(seed, philox.seq_uid(int(uids[q]), j), t)
+                ok += int(sampler.sample_token(lg[t], wl.temperature, u)[0] == tokens[q, a, t])
+                tot += 1
+    return ok, tot
+
+
 def test_c1_whole_step_matches_oracle():
     wl = workloads.WORKLOADS["C1"]
     say("C1 whole step")
@@ -159,9 +175,19 @@ def test_bound_pipeline_equals_unbound_steps_fp32():
         assert np.array_equal(nxt["advantages"].cpu().numpy(), u["advantages"])
         assert np.array_equal(nxt["union_rewards"].cpu().numpy(), u["union_rewards"])
         assert nxt["rows"] == (P * wl.n_pilot if b + 1 < len(batches) else 0) + len(kept) * wl.n_commit
-    # and the middle batch against the oracle directly
-    assert np.array_equal(outs[1]["pilot_tokens"].cpu().numpy(), want_oracle["pilot_tokens"]) or \
-        not np.array_equal(unbound[1]["pilot_tokens"], want_oracle["pilot_tokens"])
+    # and the middle batch against the oracle directly: free-running tokens where the two sides never part
+    # (the usual case on this fp32 model), and in any case every pilot and commit token teacher-forced
+    if np.array_equal(outs[1]["pilot_tokens"].cpu().numpy(), want_oracle["pilot_tokens"]):
+        assert np.array_equal(outs[1]["p_hat"], want_oracle["p_hat"])
+        assert np.array_equal(batches[1][1][want_oracle["commit_idx"]], outs[2]["commit_uids"])
+    ok, tot = _teacher_forced_agreement(wl, w, batches[1][0], batches[1][1], outs[1]["pilot_tokens"].cpu().numpy(),
+                                        range(wl.n_pilot), wl.seed_sampler)
+    assert ok >= math.ceil(0.999 * tot)
+    kept_rows = [int(np.nonzero(batches[1][1] == u)[0][0]) for u in outs[2]["commit_uids"]]
+    ok, tot = _teacher_forced_agreement(wl, w, batches[1][0][kept_rows], batches[1][1][kept_rows],
+                                        outs[2]["commit_tokens"].cpu().numpy(),
+                                        range(wl.n_pilot, wl.n_pilot + wl.n_commit), wl.seed_sampler)
+    assert ok >= math.ceil(0.999 * tot)
     total = sum(o["tokens_generated"] for o in outs)
     assert total == sum(u["tokens_generated"] for u in unbound)
 
@@ -215,3 +241,62 @@ def test_bound_pipeline_with_cap_and_delay():
     assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1]
     ctx.close()
     assert want.stats["aged_out"] > 0 and 0 in ages_seen and max(ages_seen) >= 1
+
+
+def test_bound_pipeline_16bit_against_the_oracle():
+    # the bound pipeline on the matrix-core path (bf16 weights, half activations): every pilot and commit token
+    # teacher-forced against the oracle's own logits, allocation bit-exact given the rewards.  The agreement bound
+    # is the >= 99 % the acceptance names: at this vocabulary (2048) the logit error of the half pipeline
+    # (rms 1.4e-4) moves a CDF boundary across the uniform on about 0.25 % of positions.
+    import paper_2605_26606_amd as pc
+    base = workloads.WORKLOADS["C1"]
+    wl = workloads.scaled(base, dtype="bf16", d_model=256, n_q_heads=12, n_kv_heads=2, head_dim=128, d_ff=640, vocab=2048,
+                          n_layers=3, rope_theta=1.0e6, n_prompts=6, prompt_len=40, new_tokens=10)
+    say("bound pipeline, bf16 model / half activations, 2 sampling batches")
+    w = workloads.perturb_norm_gains(workloads.make_weights(wl.model, 3), 10)
+    kw = dict(block_size=64, kv_pool_bytes=256 << 20, max_slots=128, max_ctx=128, max_batch_rows=512)
+    P, Lp = wl.n_prompts, wl.prompt_len
+    batches = [(workloads.make_prompts(P, Lp, wl.model.vocab, 50 + b), workloads.make_prompt_uids(P, first=100 * b))
+               for b in range(2)]
+    ctx = make_ctx(wl.model, w, **kw)
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    outs = []
+    with torch.cuda.stream(side_stream()):
+        pipe = pc.BoundPipeline(ctx, wl, 77)
+        for pr, uids in batches:
+            outs.append(pipe.step(torch.from_numpy(pr.reshape(-1).astype(np.int32)).cuda(), cu, uids))
+        outs.append(pipe.step(None, None, None))
+        pipe.close()
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1]
+    assert pc.pc_saturation_count(ctx) == 0
+    ctx.close()
+    ok = tot = 0
+    for b, (pr, uids) in enumerate(batches):
+        o, nxt = outs[b], outs[b + 1]
+        ptok = o["pilot_tokens"].cpu().numpy()
+        a, n = _teacher_forced_agreement(wl, w, pr, uids, ptok, range(wl.n_pilot), 77)
+        ok, tot = ok + a, tot + n
+        # rewards follow the rule, p_hat / classes / selection follow the rewards, bit-exactly
+        want_r = (ptok[:, :, -1] % 2 == 0).astype(np.float32)
+        assert np.array_equal(o["pilot_rewards"].cpu().numpy(), want_r)
+        off = (np.arange(P + 1) * wl.n_pilot).astype(np.int32)
+        p_hat = allocation.group_stats(want_r.reshape(-1), off)[2]
+        assert np.array_equal(o["p_hat"], p_hat)
+        cls, evict, commit, _, _ = allocation.select_commit(p_hat, wl.p_lower, wl.p_upper, wl.p_solve, 0)
+        assert np.array_equal(o["cls"], cls) and np.array_equal(o["evict"], evict)
+        assert np.array_equal(o["selected_uids"], uids[commit])
+        # the commit pass of this batch ran inside the next step
+        assert np.array_equal(nxt["commit_uids"], uids[commit])
+        ctok = nxt["commit_tokens"].cpu().numpy()
+        a, n = _teacher_forced_agreement(wl, w, pr[commit], uids[commit], ctok,
+                                         range(wl.n_pilot, wl.n_pilot + wl.n_commit), 77)
+        ok, tot = ok + a, tot + n
+        want_cr = (ctok[:, :, -1] % 2 == 0).astype(np.float32)
+        union = np.concatenate([want_r[commit], want_cr], axis=1)
+        assert np.array_equal(nxt["union_rewards"].cpu().numpy(), union)
+        K = len(commit)
+        adv, mu, sg = allocation.advantages(union.reshape(-1), (np.arange(K + 1) * 8).astype(np.int32))
+        assert np.array_equal(nxt["advantages"].cpu().numpy().reshape(-1), adv)
+    say("bound pipeline, 16-bit: %d/%d tokens from the oracle's own logits" % (ok, tot))
+    assert tot >= 600 and ok >= math.ceil(0.99 * tot)

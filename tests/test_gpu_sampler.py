@@ -92,3 +92,33 @@ def test_distribution_over_many_steps():
     counts = np.bincount(tok, minlength=V)
     chi2 = float(((counts - n * p) ** 2 / (n * p)).sum())
     assert chi2 < 100.0            # 39 dof
+
+
+def test_history_destinations():
+    # the token and its log-probability also go to a second place, at a caller-given index (the [step][sequence]
+    # history of a decode batch that has shrunk); rows finished on entry file eos_id / 0 there too
+    import paper_2605_26606_amd as pc
+    V, n, n_orig = 700, 9, 20
+    rng = np.random.default_rng(5)
+    logits = torch.from_numpy(rng.standard_normal((n, V)).astype(np.float32)).cuda()
+    uids = torch.arange(n, dtype=torch.int64, device="cuda") + 50
+    index = torch.from_numpy(rng.permutation(n_orig)[:n].astype(np.int32)).cuda()
+    fin = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    fin[2] = 1
+    tok = torch.zeros(n, dtype=torch.int32, device="cuda")
+    lp = torch.zeros(n, device="cuda")
+    ht = torch.full((n_orig,), -9, dtype=torch.int32, device="cuda")
+    hl = torch.full((n_orig,), 7.0, device="cuda")
+    pc.pc_sample(logits, None, n, V, 1.0, 3, uids, None, 4, 11, 0.0, tok, lp, fin, hist_tokens=ht, hist_logprob=hl,
+                 hist_index=index)
+    torch.cuda.synchronize()
+    idx = index.long()
+    assert torch.equal(ht[idx], tok) and torch.equal(hl[idx], lp) and tok[2] == 11 and lp[2] == 0
+    untouched = torch.ones(n_orig, dtype=torch.bool, device="cuda")
+    untouched[idx] = False
+    assert (ht[untouched] == -9).all() and (hl[untouched] == 7.0).all()
+    # without an index: row i
+    ht2 = torch.full((n,), -9, dtype=torch.int32, device="cuda")
+    pc.pc_sample(logits, None, n, V, 1.0, 3, uids, None, 4, 11, 0.0, tok, None, None, hist_tokens=ht2)
+    torch.cuda.synchronize()
+    assert torch.equal(ht2, tok)

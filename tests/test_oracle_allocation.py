@@ -152,3 +152,18 @@ def test_sampling_cost_matches_paper_tables(golden_dir):
         assert al.sampling_cost("dapo", 128, n=n, s=3) == dapo
         assert al.sampling_cost("pc", 128, s=3, n_pilot=npil, n_commit=ncom) == pc
     assert al.rollouts_generated(64, 4, 29, 4) == 64 * 4 + 29 * 4
+
+
+def test_rollouts_generated_reproduces_the_printed_per_step_counts(golden_dir):
+    # a step whose sampling batch holds b_g = 3 * 128 prompts and whose commit pass keeps exactly b_t = 128
+    # generates what the paper prints for Pilot-Commit (Section 4.3; the runtime table; Appendix A.4);
+    # and a step that keeps nobody costs the pilot pass alone, b_g * n_pilot
+    import os
+    for line in open(os.path.join(golden_dir, "sampling_cost.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        n, n_pilot, n_commit, grpo, pc_count, dapo = map(int, line.split())
+        assert al.rollouts_generated(3 * 128, n_pilot, 128, n_commit) == pc_count
+        assert al.rollouts_generated(3 * 128, n_pilot, 0, n_commit) == 3 * 128 * n_pilot
+        # the same budget spent without a pilot stage: every prompt of the training batch gets n rollouts
+        assert al.rollouts_generated(128, n_pilot, 128, n_commit) == grpo

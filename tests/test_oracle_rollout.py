@@ -3,7 +3,7 @@ pinned elsewhere; here the wiring (uids, steps, union groups, counts)."""
 import numpy as np
 
 import workloads
-from oracle import allocation, decoder, philox, rollout, sampler
+from oracle import allocation, decoder, philox, rewards, rollout, sampler
 
 WL = workloads.WORKLOADS["C1"]
 
@@ -80,3 +80,35 @@ def test_class_fractions_beta_bernoulli():
     assert abs(counts[2] / P - 35 / 128) < 0.012
     assert abs(counts[0] / P - 58 / 128) < 0.012
     assert evict.sum() == counts[2]
+
+
+def test_reward_rules_worked_examples():
+    # each rule on inputs worked by hand from the workload descriptions (none of these repeats the rule's
+    # own expression): "1 if the last sampled token id is even"
+    for tok, want in ((10, 1.0), (7, 0.0), (0, 1.0), (151935, 0.0), (151934, 1.0)):
+        assert rewards.reward("last_even", last_tok=tok) == want
+    # "1 if the token id at position -1 mod 7 equals the prompt id mod 7":
+    #   15 = 2*7 + 1 and 8 = 7 + 1 agree; 15 against 9 = 7 + 2 does not; 7 and 0 are both multiples of 7;
+    #   13 = 7 + 6 against 6; 3 against 10 = 7 + 3; 151935 = 21705*7 + 0 against 14; 100 = 14*7 + 2 against 3
+    for tok, uid, want in ((15, 8, 1.0), (15, 9, 0.0), (7, 0, 1.0), (13, 6, 1.0), (3, 10, 1.0), (151935, 14, 1.0),
+                           (100, 3, 0.0), (6, 7, 0.0), (1, 7, 0.0), (0, 7, 1.0)):
+        assert rewards.reward("last_mod7", last_tok=tok, prompt_uid=uid) == want
+    # Bernoulli(p) from a uniform on [0,1): success exactly when the uniform falls below p
+    for u, p, want in ((0.25, 0.5, 1.0), (0.5, 0.5, 0.0), (0.75, 0.5, 0.0), (0.0, 0.0, 0.0), (0.0, 1e-9, 1.0),
+                       (0.999999, 1.0, 1.0), (0.3, 0.29999, 0.0)):
+        assert rewards.reward("bernoulli", p_q=p, u=u) == want
+    # success frequency over many uniforms is p
+    us = workloads.make_reward_uniforms(1, 40000, 3)[0]
+    for p in (0.1, 0.5, 0.83):
+        f = np.mean([rewards.reward("bernoulli", p_q=p, u=float(x)) for x in us])
+        assert abs(f - p) < 4 * np.sqrt(p * (1 - p) / len(us))
+    # the last generated token of a sequence that stopped on EOS is the EOS itself (padding after it is ignored)
+    assert rewards.last_token(np.array([5, 9, 4, -1, -1]), 3) == 4
+    assert rewards.last_token(np.array([5, 9, 4, 8, 2]), 5) == 2
+    assert rewards.last_token(np.array([5]), 1) == 5
+    # and score_group applies the rule to exactly that token, per rollout
+    toks = np.array([[2, 4, 9, -1], [2, 4, 9, 6]])
+    got = rollout.score_group("last_even", toks, np.array([3, 4]), prompt_uid=0)
+    assert got.tolist() == [0.0, 1.0]
+    got = rollout.score_group("last_mod7", toks, np.array([3, 4]), prompt_uid=9)   # 9 = 7 + 2; 9 mod 7 = 2, 6 mod 7 = 6
+    assert got.tolist() == [1.0, 0.0]
