@@ -10,6 +10,11 @@ pc_advantages.
                   Algorithm 1 eviction {q : p_hat >= p_solve}; Section 3.3
                   cap of b_t on the committed prompts, surplus survivors kept
                   aside (for the replay buffer)
+  select_commit_variance
+                  the same filter on the group variance itself, for rewards
+                  that are not binary (Introduction, Section 3.3, Section 7:
+                  the paper names the extension, the rule is this build's
+                  reading)
   advantages      Section 3.1: A_i = (r_i - mu) / sigma over the union of a
                   kept prompt's pilot and commit rollouts (Section 3.3,
                   "Training")
@@ -83,6 +88,52 @@ def select_commit(p_hat, p_lower, p_upper, p_solve, b_t=0):
             else:
                 surplus.append(q)
         if ph[q] >= so:
+            evict[q] = 1
+    counts = np.array([len(commit), len(surplus), int(np.sum(cls == EASY)), int(np.sum(cls == HARD))], np.int32)
+    return cls, evict, np.asarray(commit, np.int32), np.asarray(surplus, np.int32), counts
+
+
+def select_commit_variance(mean, var, var_hard, var_easy, mean_pivot, mean_solve, b_t=0):
+    """Pilot filter for rewards that are not binary, on the pilot group's mean
+    and population variance (fp32, as group_stats returns them).
+
+    The paper defines the filter for binary rewards only and says that it
+    extends to any scalar reward, with the variance as the measure of a
+    prompt's informativeness (Introduction; Section 3.3; Section 7).  The
+    reading taken here keeps the two things Section 3.3 argues for -- select on
+    the variance, and be more lenient with prompts that still approach the
+    high-variance regime than with prompts that have passed it:
+
+      keep[q]  = var >= var_hard   if mean <= mean_pivot   (approaching)
+                 var >= var_easy   if mean >  mean_pivot   (leaving)
+      cls[q]   = KEEP if kept, else HARD if mean <= mean_pivot, else EASY
+      evict[q] = mean >= mean_solve
+      commit / surplus: as in select_commit.
+
+    With 0/1 rewards, mean_pivot = 1/2, var_hard = p_lower (1 - p_lower) and
+    var_easy = p_upper (1 - p_upper) (p_lower <= 1/2 <= p_upper) this is the
+    binary filter p_lower <= p_hat <= p_upper, since p (1 - p) rises up to 1/2
+    and falls beyond it.  All comparisons in fp32."""
+    mu = np.asarray(mean, dtype=np.float32)
+    vr = np.asarray(var, dtype=np.float32)
+    vh, ve = np.float32(var_hard), np.float32(var_easy)
+    pv, so = np.float32(mean_pivot), np.float32(mean_solve)
+    P = len(mu)
+    cls = np.empty(P, np.uint8)
+    evict = np.zeros(P, np.uint8)
+    commit, surplus = [], []
+    for q in range(P):
+        approaching = mu[q] <= pv
+        kept = (vr[q] >= vh) if approaching else (vr[q] >= ve)
+        if kept:
+            cls[q] = KEEP
+            if b_t <= 0 or len(commit) < b_t:
+                commit.append(q)
+            else:
+                surplus.append(q)
+        else:
+            cls[q] = HARD if approaching else EASY
+        if mu[q] >= so:
             evict[q] = 1
     counts = np.array([len(commit), len(surplus), int(np.sum(cls == EASY)), int(np.sum(cls == HARD))], np.int32)
     return cls, evict, np.asarray(commit, np.int32), np.asarray(surplus, np.int32), counts

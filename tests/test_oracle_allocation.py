@@ -167,3 +167,92 @@ def test_rollouts_generated_reproduces_the_printed_per_step_counts(golden_dir):
         assert al.rollouts_generated(3 * 128, n_pilot, 0, n_commit) == 3 * 128 * n_pilot
         # the same budget spent without a pilot stage: every prompt of the training batch gets n rollouts
         assert al.rollouts_generated(128, n_pilot, 128, n_commit) == grpo
+
+
+# ---------------------------------------------------------------- rewards that are not binary
+
+def test_variance_filter_reduces_to_the_binary_filter():
+    # 0/1 rewards, thresholds p (1 - p) at the paper's p_lower / p_upper, pivot 1/2: the same classes, eviction
+    # flags, commit set and counts as the binary filter, for every k at n = 4, 8, 16, 32 (Section 4.2 thresholds;
+    # the boundary cases k/n = 0.125 and 0.75 are kept by both)
+    for n in (4, 8, 16, 32):
+        groups = [np.random.default_rng(k).permutation(_binary_group(n, k)) for k in range(n + 1)]
+        off = (np.arange(n + 2) * n).astype(np.int32)
+        _, _, mean, var = al.group_stats(np.concatenate(groups), off)
+        for b_t in (0, 3):
+            want = al.select_commit(mean, 0.125, 0.75, 1.0, b_t)
+            got = al.select_commit_variance(mean, var, 0.125 * 0.875, 0.75 * 0.25, 0.5, 1.0, b_t)
+            for a, b in zip(want, got):
+                assert np.array_equal(a, b)
+    # and for random thresholds on either side of 1/2, away from the boundaries
+    rng = np.random.default_rng(1)
+    for _ in range(50):
+        n = int(rng.integers(2, 40))
+        lo, hi = rng.uniform(0.01, 0.49), rng.uniform(0.51, 0.99)
+        k = np.arange(n + 1)
+        if np.min(np.abs(k / n - lo)) < 1e-3 or np.min(np.abs(k / n - hi)) < 1e-3:
+            continue
+        groups = [_binary_group(n, kk) for kk in k]
+        _, _, mean, var = al.group_stats(np.concatenate(groups), (np.arange(n + 2) * n).astype(np.int32))
+        want = al.select_commit(mean, lo, hi, 1.0)
+        got = al.select_commit_variance(mean, var, lo * (1 - lo), hi * (1 - hi), 0.5, 1.0)
+        for a, b in zip(want, got):
+            assert np.array_equal(a, b)
+
+
+def test_variance_filter_multi_valued_rewards_closed_forms():
+    # three-valued rewards {0, 1/2, 1}: Var = sum f_v v^2 - mean^2 with f_v the fraction of each value
+    groups = {
+        "half/half 0 and 1":        ([0, 1, 0, 1],             0.5,   0.25),
+        "all one half":             ([.5, .5, .5, .5],         0.5,   0.0),
+        "0, 1/2, 1, 1/2":           ([0, .5, 1, .5],           0.5,   0.125),
+        "mostly 1/2, one 1":        ([.5, .5, .5, 1],          0.625, 0.046875),
+        "mostly 0, one 1/2":        ([0, 0, 0, .5],            0.125, 0.046875),
+        "mostly 1, one 0":          ([1, 1, 1, 0],             0.75,  0.1875),
+        "all 1":                    ([1, 1, 1, 1],             1.0,   0.0),
+    }
+    r = np.concatenate([np.asarray(g[0], np.float32) for g in groups.values()])
+    off = (np.arange(len(groups) + 1) * 4).astype(np.int32)
+    _, _, mean, var = al.group_stats(r, off)
+    assert mean.tolist() == [g[1] for g in groups.values()]
+    assert var.tolist() == [g[2] for g in groups.values()]
+    cls, evict, commit, surplus, counts = al.select_commit_variance(mean, var, 0.04, 0.1, 0.5, 1.0)
+    #        0/1 mix   all 1/2 (no spread, mean at the pivot: "approaching")   spread   leaving, too little spread
+    assert cls.tolist() == [al.KEEP, al.HARD, al.KEEP, al.EASY, al.KEEP, al.KEEP, al.EASY]
+    assert evict.tolist() == [0, 0, 0, 0, 0, 0, 1]
+    assert commit.tolist() == [0, 2, 4, 5] and counts.tolist() == [4, 0, 2, 1]
+    # a cap keeps the first two in batch order, the rest is surplus
+    cls2, _, commit2, surplus2, counts2 = al.select_commit_variance(mean, var, 0.04, 0.1, 0.5, 1.0, b_t=2)
+    assert commit2.tolist() == [0, 2] and surplus2.tolist() == [4, 5] and counts2.tolist() == [2, 2, 2, 1]
+    assert np.array_equal(cls2, cls)
+
+
+def test_variance_filter_edges_and_scaling():
+    # inclusive thresholds, +-1 ulp
+    v = np.float32(0.1)
+    below, above = np.nextafter(v, np.float32(0)), np.nextafter(v, np.float32(1))
+    mean = np.array([0.3, 0.3, 0.3, 0.7, 0.7, 0.7], np.float32)
+    var = np.array([below, v, above, below, v, above], np.float32)
+    cls, _, _, _, _ = al.select_commit_variance(mean, var, 0.1, 0.1, 0.5, 2.0)
+    assert cls.tolist() == [al.HARD, al.KEEP, al.KEEP, al.EASY, al.KEEP, al.KEEP]
+    # the pivot itself counts as "approaching" (<=)
+    half = np.float32(0.5)
+    cls, _, _, _, _ = al.select_commit_variance([half, np.nextafter(half, np.float32(1))], [0.05, 0.05], 0.04, 0.06, 0.5, 2.0)
+    assert cls.tolist() == [al.KEEP, al.EASY]
+    # rewards scaled by 4 (exactly representable): variance scales by 16, mean and pivot by 4: same selection
+    rng = np.random.default_rng(2)
+    r = rng.integers(0, 5, 64 * 8).astype(np.float32) / 4.0
+    off = (np.arange(65) * 8).astype(np.int32)
+    _, _, m1, v1 = al.group_stats(r, off)
+    _, _, m4, v4 = al.group_stats(4.0 * r, off)
+    a = al.select_commit_variance(m1, v1, 0.08, 0.11, 0.5, 0.9, 5)
+    b = al.select_commit_variance(m4, v4, 16 * 0.08, 16 * 0.11, 2.0, 3.6, 5)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    assert 0 < a[4][0] and a[4][2] > 0 and a[4][3] > 0          # all three classes occur
+    # evict: mean >= mean_solve, independent of the class
+    _, evict, _, _, _ = al.select_commit_variance([0.9, 1.0, 1.0], [0.2, 0.0, 0.3], 0.1, 0.1, 0.5, 1.0)
+    assert evict.tolist() == [0, 1, 1]
+    # empty batch
+    out = al.select_commit_variance([], [], 0.1, 0.1, 0.5, 1.0)
+    assert len(out[0]) == 0 and out[4].tolist() == [0, 0, 0, 0]

@@ -2,6 +2,7 @@
 import math
 
 import numpy as np
+import pytest
 
 from oracle import philox, sampler
 
@@ -77,3 +78,70 @@ def test_distribution_chi_square():
         counts[sampler.sample_token(logits, 1.0, philox.sampling_uniform(42, 7, t))[0]] += 1
     chi2 = float(((counts - n * p) ** 2 / (n * p)).sum())
     assert chi2 < 70.0          # 23 dof: mean 23, sd 6.8
+
+
+# ---------------------------------------------------------------- nucleus (top-p) truncation
+
+def test_top_p_one_is_the_plain_sampler():
+    rng = np.random.default_rng(3)
+    logits = (2.0 * rng.standard_normal(500)).astype(np.float32)
+    for u in rng.random(40):
+        assert sampler.sample_token(logits, 0.7, u, top_p=1.0) == sampler.sample_token(logits, 0.7, u)
+    assert sampler.nucleus(np.exp(logits.astype(np.float64)), 1.0).all()
+
+
+def test_top_p_three_token_worked_example():
+    # probabilities (0.5, 0.3, 0.2).  top_p = 0.7: 0.5 < 0.7 <= 0.5 + 0.3, so tokens {0, 1} stay and are
+    # renormalised to (0.625, 0.375); token 2 is never drawn.  top_p = 0.5: token 0 alone reaches it.
+    # top_p = 0.81: all three are needed.
+    lg = np.log(np.array([0.5, 0.3, 0.2]))
+    for u in np.linspace(0.002, 0.998, 250):
+        tok, lp = sampler.sample_token(lg, 1.0, u, top_p=0.7)
+        assert tok == (0 if u < 0.625 else 1)
+        assert abs(lp - math.log(0.625 if tok == 0 else 0.375)) < 1e-6
+        assert sampler.sample_token(lg, 1.0, u, top_p=0.5) == (0, pytest.approx(0.0, abs=1e-6))
+        tok3, lp3 = sampler.sample_token(lg, 1.0, u, top_p=0.81)
+        assert tok3 == (0 if u < 0.5 else 1 if u < 0.8 else 2)
+        assert abs(lp3 - math.log([0.5, 0.3, 0.2][tok3])) < 1e-6
+    # the kept tokens need not be a prefix in id order: (0.2, 0.5, 0.3) keeps ids {1, 2}, sampled in id order
+    lg2 = np.log(np.array([0.2, 0.5, 0.3]))
+    for u in np.linspace(0.002, 0.998, 250):
+        assert sampler.sample_token(lg2, 1.0, u, top_p=0.7)[0] == (1 if u < 0.625 else 2)
+
+
+def test_top_p_ties_keep_the_lower_ids():
+    assert sampler.nucleus(np.ones(4), 0.5).tolist() == [True, True, False, False]
+    assert sampler.nucleus(np.ones(4), 0.51).tolist() == [True, True, True, False]
+    assert sampler.nucleus(np.array([1.0, 4.0, 1.0, 4.0, 1.0]), 0.8).tolist() == [True, True, False, True, False]
+
+
+def test_top_p_set_is_minimal_and_reaches_the_mass():
+    rng = np.random.default_rng(9)
+    for trial in range(20):
+        w = np.exp(3.0 * rng.standard_normal(400))
+        top_p = float(np.float32(rng.uniform(0.05, 0.99)))
+        keep = sampler.nucleus(w, top_p)
+        mass = w[keep].sum() / w.sum()
+        assert mass >= top_p - 1e-12
+        assert (w[keep].sum() - w[keep].min()) / w.sum() < top_p + 1e-12        # one token fewer falls short
+        assert w[keep].min() >= w[~keep].max()                                  # the heaviest tokens are the kept ones
+
+
+def test_top_p_distribution_and_temperature():
+    # draws at temperature 0.7 with top_p 0.9 follow the softmax at that temperature, truncated and renormalised
+    rng = np.random.default_rng(4)
+    logits = rng.standard_normal(30).astype(np.float32)
+    p = sampler.softmax_probs(logits, 0.7)
+    keep = sampler.nucleus(p, 0.9)
+    q = np.where(keep, p, 0.0)
+    q /= q.sum()
+    n = 30000
+    counts = np.zeros(30)
+    for i in range(n):
+        u = philox.sampling_uniform(17, 1000 + i, 0)
+        tok, lp = sampler.sample_token(logits, 0.7, u, top_p=0.9)
+        counts[tok] += 1
+        assert abs(lp - math.log(q[tok])) < 1e-5
+    assert counts[~keep].sum() == 0
+    chi2 = float((((counts - n * q) ** 2)[keep] / (n * q[keep])).sum())
+    assert chi2 < 3.0 * keep.sum()
