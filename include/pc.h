@@ -174,6 +174,19 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
 pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n,
                          float *logits, void *stream);
 
+/* pc_decode_step for callers that cannot allocate device memory while they run (code under HIP graph
+ * capture of their own, tight serving loops, harnesses that forbid hipMalloc): same arguments, same
+ * kernels, same results, but it calls no hipMalloc / hipFree / graph instantiation, and the scratch its
+ * kernels need beyond the inputs and outputs (the K slices of the split projections and the partial
+ * results of the context-split attention) lives in one fixed 32 MiB device array inside the library.
+ * The step is always launched eagerly.  A batch whose scratch would not fit -- 8 * n * max(q/k/v width,
+ * d_model) * 4 bytes of slices plus (n + 512) * n_q_heads * (head_dim + 2) * 4 bytes of attention
+ * partials, e.g. more than 470 sequences of the 1.5B shape -- is PC_ERR_INVALID_ARG (nothing launched).
+ * Every call on a GPU, from any context, uses that GPU's one array: calls that overlap in time on
+ * different streams race; order them.  Nothing in the array has to survive between calls. */
+pc_status pc_decode_step_static(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n,
+                                float *logits, void *stream);
+
 /* Releases sequences (kind 0) or prompts (kind 1); ids is host int32 [n].
  * Shared blocks are freed when their last user goes. */
 pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind);

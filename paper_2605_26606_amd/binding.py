@@ -79,6 +79,7 @@ def library() -> C.CDLL:
             "pc_prefill_shared": [vp, vp, vp, i32, vp, vp, vp],
             "pc_fork": [vp, vp, i32, i32, vp, vp],
             "pc_decode_step": [vp, vp, vp, i32, vp, vp],
+            "pc_decode_step_static": [vp, vp, vp, i32, vp, vp],
             "pc_release": [vp, vp, i32, i32],
             "pc_score": [vp, vp, vp, vp, i32, f32, vp, vp],
             "pc_sample": [vp, vp, i32, i32, f32, f32, u64, vp, vp, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp],
@@ -246,6 +247,17 @@ def pc_decode_step(ctx: Context, seq, tokens_in: torch.Tensor, logits: torch.Ten
         raise ValueError("tokens_in / logits too small for %d sequences" % n)
     _check(library().pc_decode_step(ctx.handle, s.ctypes.data, _dev(tokens_in, torch.int32, "tokens_in"), n,
                                     _dev(logits, torch.float32, "logits"), _stream_ptr(stream)))
+
+
+def pc_decode_step_static(ctx: Context, seq, tokens_in: torch.Tensor, logits: torch.Tensor, stream=None):
+    """pc_decode_step without any device allocation: eager launches, scratch in the library's static array."""
+    s = seq if (isinstance(seq, np.ndarray) and seq.dtype == np.int32 and seq.flags.c_contiguous and seq.ndim == 1) \
+        else _host_i32(seq, "seq")
+    n = len(s)
+    if n and (tokens_in.numel() < n or logits.numel() < n * ctx.vocab):
+        raise ValueError("tokens_in / logits too small for %d sequences" % n)
+    _check(library().pc_decode_step_static(ctx.handle, s.ctypes.data, _dev(tokens_in, torch.int32, "tokens_in"), n,
+                                           _dev(logits, torch.float32, "logits"), _stream_ptr(stream)))
 
 
 def pc_score(ctx: Context, tokens: torch.Tensor, cu_lens, prompt_len, temperature: float, logprob_out: torch.Tensor,

@@ -5,10 +5,18 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "pc_internal.h"
+
+// Scratch of pc_decode_step_static, the decode step that allocates nothing: one fixed array per GPU in the
+// library's code object (every GPU the library is loaded on holds its own copy until the process ends).
+// In host code this name is only a handle for hipGetSymbolAddress: the address kernels get is looked up once
+// per device (static_scratch_base) and that pointer is what is passed on.
+static constexpr size_t PC_STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[PC_STATIC_SCRATCH_BYTES];
 
 namespace pc {
 
@@ -131,6 +139,7 @@ struct pc_ctx {
     // of the entry point that allocates nothing
     float *cur_slices = nullptr, *cur_attn_scratch = nullptr;
     size_t cur_slice_cap = 0;
+    unsigned char *static_scratch = nullptr;   // this device's copy of the static scratch array
     uint32_t *d_sat = nullptr;     // stores clamped to the half range (KD_F16)
     Staging stage;
     std::vector<int32_t> dec_seq;     // sequence list currently resident in d_dec_slot
@@ -328,6 +337,22 @@ void enqueue_decode(pc_ctx *ctx, const int32_t *tokens_in, int n, float *logits,
     launch_advance_len(ctx->d_slot_len, ctx->d_dec_slot, n, st);
 }
 
+// Device address of the static scratch array on `device` (which must be current): looked up once per device.
+pc_status static_scratch_base(int device, unsigned char **out) {
+    static std::mutex mu;
+    static unsigned char *base[64] = {nullptr};
+    if (device < 0 || device >= 64) PC_FAIL(PC_ERR_UNSUPPORTED, "device index %d outside 0..63", device);
+    std::lock_guard<std::mutex> lock(mu);
+    if (!base[device]) {
+        void *p = nullptr;
+        PC_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) PC_FAIL(PC_ERR_HIP, "hipGetSymbolAddress returned no address for the static scratch array");
+        base[device] = (unsigned char *)p;
+    }
+    *out = base[device];
+    return PC_OK;
+}
+
 pc_status check_launch() {
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) PC_FAIL(PC_ERR_HIP, "kernel launch failed: %s", hipGetErrorString(e));
@@ -391,6 +416,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
         }                                                                                    \
     } while (0)
     TRY_HIP(hipGetDevice(&ctx->device));
+    TRY(static_scratch_base(ctx->device, &ctx->static_scratch));
     gemm_init();
     const size_t esz = ctx->esz;
     const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
@@ -857,29 +883,24 @@ pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind) {
     return PC_OK;
 }
 
-pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
-                         void *stream) {
-    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: null context");
-    if (n < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: negative count");
-    if (n == 0) return PC_OK;
-    if (!seq || !tokens_in || !logits) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: null argument");
-    if (n > ctx->c.max_batch_rows) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: n exceeds max_batch_rows");
-    hipStream_t st = (hipStream_t)stream;
+// Argument checks of a decode step and the upload of its sequence list (shared by the two entry points).
+static pc_status prepare_decode(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
+                                hipStream_t st, const char *who) {
+    if (!seq || !tokens_in || !logits) PC_FAIL(PC_ERR_INVALID_ARG, "%s: null argument", who);
+    if (n > ctx->c.max_batch_rows) PC_FAIL(PC_ERR_INVALID_ARG, "%s: n exceeds max_batch_rows", who);
     const int32_t gen = ++ctx->stamp_gen;
-    int max_len = 0;
     for (int i = 0; i < n; ++i) {
         const int s = seq[i];
         if (s < 0 || s >= ctx->c.max_slots || !ctx->slots[s].used || ctx->slots[s].is_prompt)
-            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: entry %d is not a live sequence", i);
-        if (ctx->stamp[s] == gen) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d repeats", s);
+            PC_FAIL(PC_ERR_INVALID_ARG, "%s: entry %d is not a live sequence", who, i);
+        if (ctx->stamp[s] == gen) PC_FAIL(PC_ERR_INVALID_ARG, "%s: sequence %d repeats", who, s);
         ctx->stamp[s] = gen;
         if (ctx->slots[s].len >= ctx->slots[s].limit)
-            PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: sequence %d already holds its %d tokens (prompt + reserved new tokens)",
+            PC_FAIL(PC_ERR_INVALID_ARG, "%s: sequence %d already holds its %d tokens (prompt + reserved new tokens)", who,
                     s, ctx->slots[s].limit);
-        max_len = std::max(max_len, ctx->slots[s].len);
     }
     if ((int)ctx->dec_seq.size() != n || memcmp(ctx->dec_seq.data(), seq, (size_t)n * 4) != 0) {
-        ctx->dec_seq.assign(seq, seq + n);
+        ctx->dec_seq.assign(seq, seq + n);   // within the capacity reserved at creation
         ctx->list_version++;
         // rollouts of one prompt that sit next to each other in the list share their prefix blocks
         int g = 1;
@@ -896,7 +917,26 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
             return rc;
         }
     }
-    (void)max_len;
+    return PC_OK;
+}
+
+static void advance_host_lengths(pc_ctx *ctx, const int32_t *seq, int32_t n) {
+    for (int i = 0; i < n; ++i) {
+        ctx->slots[seq[i]].len++;
+        ctx->h_len[seq[i]]++;
+    }
+}
+
+pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
+                         void *stream) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: null context");
+    if (n < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step: negative count");
+    if (n == 0) return PC_OK;
+    hipStream_t st = (hipStream_t)stream;
+    {
+        const pc_status rc = prepare_decode(ctx, seq, tokens_in, n, logits, st, "pc_decode_step");
+        if (rc != PC_OK) return rc;
+    }
     if (ctx->use_graph && st != nullptr && ctx->time_class < 0) {   // the default stream cannot be captured
         const bool hit = ctx->exec && ctx->gkey.n == n && ctx->gkey.tokens == tokens_in && ctx->gkey.logits == logits &&
                          ctx->gkey.stream == st &&
@@ -944,10 +984,45 @@ pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_
         pc_status rc = check_launch();
         if (rc != PC_OK) return rc;
     }
-    for (int i = 0; i < n; ++i) {
-        ctx->slots[seq[i]].len++;
-        ctx->h_len[seq[i]]++;
+    advance_host_lengths(ctx, seq, n);
+    return PC_OK;
+}
+
+pc_status pc_decode_step_static(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
+                                void *stream) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step_static: null context");
+    if (n < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_decode_step_static: negative count");
+    if (n == 0) return PC_OK;
+    hipStream_t st = (hipStream_t)stream;
+    // what the step's kernels may use of the static array: the K slices of the split projections (at most 8
+    // slices of n rows of the widest split output) and the partial results of the split attention
+    const pc_model_config &m = ctx->m;
+    const size_t width = (size_t)std::max(m.n_q_heads * m.head_dim + 2 * m.n_kv_heads * m.head_dim, m.d_model);
+    const size_t slice_floats = (size_t)8 * (size_t)n * width;
+    const size_t attn_floats = attention_decode_scratch_floats(n, m.n_q_heads, m.head_dim);
+    const size_t slice_bytes = (slice_floats * sizeof(float) + 255) / 256 * 256;
+    const size_t need = slice_bytes + attn_floats * sizeof(float);
+    if (need > PC_STATIC_SCRATCH_BYTES)
+        PC_FAIL(PC_ERR_INVALID_ARG,
+                "pc_decode_step_static: %d sequences of this model need %zu bytes of scratch, the static array holds %zu "
+                "(use pc_decode_step)", n, need, PC_STATIC_SCRATCH_BYTES);
+    {
+        const pc_status rc = prepare_decode(ctx, seq, tokens_in, n, logits, st, "pc_decode_step_static");
+        if (rc != PC_OK) return rc;
     }
+    // same kernels, same launch shapes and the same K-slice decisions as pc_decode_step (cur_slice_cap keeps the
+    // context's value; the slices actually written never exceed slice_floats), only the scratch is the static array
+    const int saved_time_class = ctx->time_class;
+    ctx->time_class = -1;   // per-launch event timing creates events: not here
+    ctx->cur_slices = (float *)ctx->static_scratch;
+    ctx->cur_attn_scratch = (float *)(ctx->static_scratch + slice_bytes);
+    enqueue_decode(ctx, tokens_in, n, logits, st);
+    ctx->cur_slices = ctx->slices;
+    ctx->cur_attn_scratch = ctx->attn_scratch;
+    ctx->time_class = saved_time_class;
+    const pc_status rc = check_launch();
+    if (rc != PC_OK) return rc;
+    advance_host_lengths(ctx, seq, n);
     return PC_OK;
 }
 
