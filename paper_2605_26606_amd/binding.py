@@ -20,6 +20,7 @@ _LIB_PATH = os.path.join(_HERE, "libpc.so")
 PC_OPT_USE_GRAPH = 1
 PC_OPT_FORCE_SIMT = 2
 PC_OPT_TIME_NEXT_STEP = 3
+PC_OPT_FUSE_DECODE = 4
 PC_KERNEL_ATTN_DECODE, PC_KERNEL_GEMM_QKV, PC_KERNEL_GEMM_WO = 0, 1, 2
 PC_KERNEL_GEMM_GATE_UP, PC_KERNEL_GEMM_DOWN, PC_KERNEL_GEMM_LM_HEAD = 3, 4, 5
 _DTYPES = {"fp32": 0, "bf16": 1}

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpc.so")
 KERNEL_BENCH = os.path.join(HERE, "kernel_bench")   # standalone driver of the hot kernels (tuning, counter runs)
-SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "attention.hip", "sampler.hip", "allocation.hip", "scheduler.hip"]
+SOURCES = ["api.hip", "elementwise.hip", "gemm.hip", "gemm_skinny.hip", "attention.hip", "sampler.hip", "allocation.hip", "scheduler.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -131,6 +131,11 @@ struct pc_ctx {
     float *score_logits = nullptr;    // pc_score: logits of score_rows rows at a time (allocated on first use)
     int score_rows = 0;
     void *a = nullptr, *q = nullptr, *attn = nullptr, *act = nullptr;
+    void *h_act = nullptr;          // activation-type copy of the residual rows (fused decode path)
+    float *ssq = nullptr;           // [d_model / 32][rows] partial sums of squares of the residual rows
+    // 16-bit models: the library's weight copies are laid out for the fused decode kernels
+    bool qkv_perm = false;          // q and k head rows in the order of qkv_packed_dim
+    int fuse_decode = 1;            // PC_OPT_FUSE_DECODE
     int32_t *d_meta = nullptr;   // row_slot | row_pos | cu_rows | prompt_slot | last_rows | copy pairs
     int32_t *d_dec_slot = nullptr;
     float *slices = nullptr;       // split-K slices of the decode projections
@@ -202,6 +207,7 @@ void free_all(pc_ctx *ctx) {
     fr(ctx->pool); fr(ctx->d_block_table); fr(ctx->d_slot_len); fr(ctx->rope_cos); fr(ctx->rope_sin);
     fr(ctx->h); fr(ctx->qkv); fr(ctx->attn_scratch); fr(ctx->score_logits); fr(ctx->a); fr(ctx->q); fr(ctx->attn); fr(ctx->act);
     fr(ctx->d_meta); fr(ctx->d_dec_slot); fr(ctx->slices); fr(ctx->lm_head_copy); fr(ctx->d_sat);
+    fr(ctx->h_act); fr(ctx->ssq);
     ctx->stage.destroy();
 }
 
@@ -273,9 +279,47 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
     const int n_splits = attention_decode_splits(rows, m.n_kv_heads, ctx->c.max_ctx);
     uint32_t *sat = ctx->d_sat;
     int pending = 1;
+    // Decode batches of a 16-bit model on the matrix-core path: six launches per layer instead of eight.  The q/k/v
+    // projection rotates q and k and appends k and v itself; the output projection updates the residual stream and
+    // leaves the new rows times the next RMSNorm's gain plus that norm's row statistics, and the gate/up epilogue
+    // applies the norm's scale.
+    const bool fused = !row_pos && ctx->fuse_decode && impl == 1 && ctx->mfma_attention() && ctx->qkv_perm &&
+                       skinny_ok(rows, qd + 2 * kvd, m.d_model, m.head_dim) &&
+                       skinny_ok(rows, m.d_model, qd, m.head_dim);
     for (int l = 0; l < m.n_layers; ++l) {
         launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, pending,
                        sat, st);
+        if (fused) {
+            {
+                Timed t(ctx, PC_KERNEL_GEMM_QKV, st);
+                launch_skinny_qkv(dt, ctx->a, ctx->wqkv[l], rows, m.d_model, row_slot, ctx->d_slot_len, ctx->rope_cos,
+                                  ctx->rope_sin, m.n_q_heads, kv, l, ctx->q, sat, st);
+            }
+            {
+                Timed t(ctx, PC_KERNEL_ATTN_DECODE, st);
+                launch_attention_decode_mfma(dt, ctx->q, row_slot, ctx->d_slot_len, rows, m.n_q_heads, kv, l, n_splits,
+                                             ctx->dec_group, ctx->cur_attn_scratch, ctx->attn, sat, st);
+            }
+            launch_attention_decode_merge(dt, row_slot, ctx->d_slot_len, rows, m.n_q_heads, m.n_kv_heads, n_splits,
+                                          ctx->cur_attn_scratch, ctx->attn, sat, st);
+            {
+                Timed t(ctx, PC_KERNEL_GEMM_WO, st);
+                launch_skinny_o(dt, ctx->attn, ctx->wo[l], rows, m.d_model, qd, ctx->h, ctx->ffn_norm[l], ctx->h_act, ctx->ssq,
+                                sat, st);
+            }
+            {
+                Timed t(ctx, PC_KERNEL_GEMM_GATE_UP, st);
+                const GemmRowScale rsc{ctx->ssq, m.d_model / 32, m.d_model, m.rms_eps};
+                launch_gemm(dt, impl, ctx->h_act, ctx->wgu[l], ctx->act, rows, 2 * m.d_ff, m.d_model, EPI_SWIGLU_RS, nullptr,
+                            0, sat, st, &rsc);
+            }
+            {
+                Timed t(ctx, PC_KERNEL_GEMM_DOWN, st);
+                pending = launch_gemm(dt, impl, ctx->act, ctx->wdown[l], ctx->h, rows, m.d_model, m.d_ff, EPI_RESID_F32,
+                                      ctx->cur_slices, ctx->cur_slice_cap, sat, st);
+            }
+            continue;
+        }
         int s_qkv;
         {
             Timed t(ctx, PC_KERNEL_GEMM_QKV, st);
@@ -283,7 +327,7 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
                                 ctx->cur_slices, ctx->cur_slice_cap, sat, st);
         }
         launch_rope_append(dt, s_qkv > 1 ? ctx->cur_slices : ctx->qkv, s_qkv, row_slot, row_pos, ctx->d_slot_len,
-                           ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, sat, st);
+                           ctx->rope_cos, ctx->rope_sin, rows, m.n_q_heads, kv, l, ctx->q, sat, ctx->qkv_perm ? 1 : 0, st);
         if (ctx->mfma_attention()) {
             if (row_pos)
                 launch_attention_prefill_mfma(dt, ctx->q, cu_rows, prompt_slot, n_prompts, max_len, m.n_q_heads, kv, l,
@@ -395,6 +439,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     ctx->c = *cache;
     ctx->esz = (m.dtype == PC_DTYPE_F32) ? 4 : 2;
     ctx->kd = (m.dtype == PC_DTYPE_F32) ? KD_F32 : (m.act_dtype == PC_ACT_BF16 ? KD_BF16 : KD_F16);
+    ctx->qkv_perm = ctx->kd != KD_F32 && m.head_dim == 128;
     pc_status rc = PC_OK;
 #define TRY(expr)                 \
     do {                          \
@@ -418,6 +463,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     TRY_HIP(hipGetDevice(&ctx->device));
     TRY(static_scratch_base(ctx->device, &ctx->static_scratch));
     gemm_init();
+    skinny_init();
     const size_t esz = ctx->esz;
     const int qd = m.n_q_heads * m.head_dim, kvd = m.n_kv_heads * m.head_dim;
     hipStream_t st = nullptr;
@@ -431,18 +477,18 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
         float *g;
         TRY(dev_alloc((char **)&p, (size_t)(qd + 2 * kvd) * m.d_model * esz));
         ctx->wqkv.push_back(p);
-        launch_pack_rows(ctx->kd, w->wq[l], p, qd, m.d_model, 0, st);
-        launch_pack_rows(ctx->kd, w->wk[l], p, kvd, m.d_model, qd, st);
-        launch_pack_rows(ctx->kd, w->wv[l], p, kvd, m.d_model, qd + kvd, st);
+        launch_pack_rows(ctx->kd, w->wq[l], p, qd, m.d_model, 0, ctx->qkv_perm ? m.head_dim : 0, st);
+        launch_pack_rows(ctx->kd, w->wk[l], p, kvd, m.d_model, qd, ctx->qkv_perm ? m.head_dim : 0, st);
+        launch_pack_rows(ctx->kd, w->wv[l], p, kvd, m.d_model, qd + kvd, 0, st);
         TRY(dev_alloc((char **)&p, (size_t)m.d_model * qd * esz));
         ctx->wo.push_back(p);
-        launch_pack_rows(ctx->kd, w->wo[l], p, m.d_model, qd, 0, st);
+        launch_pack_rows(ctx->kd, w->wo[l], p, m.d_model, qd, 0, 0, st);
         TRY(dev_alloc((char **)&p, (size_t)2 * m.d_ff * m.d_model * esz));
         ctx->wgu.push_back(p);
         launch_pack_gate_up(ctx->kd, w->w_gate[l], w->w_up[l], p, m.d_ff, m.d_model, st);
         TRY(dev_alloc((char **)&p, (size_t)m.d_model * m.d_ff * esz));
         ctx->wdown.push_back(p);
-        launch_pack_rows(ctx->kd, w->w_down[l], p, m.d_model, m.d_ff, 0, st);
+        launch_pack_rows(ctx->kd, w->w_down[l], p, m.d_model, m.d_ff, 0, 0, st);
         TRY(dev_alloc(&g, (size_t)m.d_model));
         ctx->attn_norm.push_back(g);
         TRY_HIP(hipMemcpyAsync(g, w->attn_norm[l], (size_t)m.d_model * 4, hipMemcpyDeviceToDevice, st));
@@ -453,7 +499,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
 
     if (ctx->kd == KD_F16) {   // the output projection is read through a half copy
         TRY(dev_alloc((char **)&ctx->lm_head_copy, (size_t)m.vocab * m.d_model * esz));
-        launch_pack_rows(ctx->kd, w->lm_head, ctx->lm_head_copy, m.vocab, m.d_model, 0, st);
+        launch_pack_rows(ctx->kd, w->lm_head, ctx->lm_head_copy, m.vocab, m.d_model, 0, 0, st);
         ctx->lm_head = ctx->lm_head_copy;
     }
 
@@ -511,6 +557,11 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     TRY(dev_alloc((char **)&ctx->q, R * qd * esz));
     TRY(dev_alloc((char **)&ctx->attn, R * qd * esz));
     TRY(dev_alloc((char **)&ctx->act, R * m.d_ff * esz));
+    if (ctx->kd != KD_F32) {
+        const size_t Rd = std::min<size_t>(R, 512);   // the fused decode path takes at most 512 rows
+        TRY(dev_alloc((char **)&ctx->h_act, Rd * m.d_model * esz));
+        TRY(dev_alloc(&ctx->ssq, Rd * (size_t)((m.d_model + 31) / 32)));
+    }
     TRY(dev_alloc(&ctx->attn_scratch,
                   attention_decode_scratch_floats(std::min<int>((int)R, cache->max_slots), m.n_q_heads, m.head_dim)));
     ctx->slice_cap = (size_t)8 << 20;   // 32 MB
@@ -547,6 +598,7 @@ pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value) {
     switch (option) {
         case PC_OPT_USE_GRAPH: ctx->use_graph = value ? 1 : 0; break;
         case PC_OPT_FORCE_SIMT: ctx->force_simt = value ? 1 : 0; break;
+        case PC_OPT_FUSE_DECODE: ctx->fuse_decode = value ? 1 : 0; break;
         case PC_OPT_TIME_NEXT_STEP:
             if (value < -1 || value > PC_KERNEL_GEMM_LM_HEAD) PC_FAIL(PC_ERR_INVALID_ARG, "pc_set_option: unknown kernel class");
             ctx->time_class = value;

@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
                                                           const float *__restrict__ rope_cos,
                                                           const float *__restrict__ rope_sin, int hq, KvGeom kv,
                                                           int layer, T *__restrict__ q_out,
-                                                          uint32_t *__restrict__ sat) {
+                                                          uint32_t *__restrict__ sat, int perm) {
     const int r = blockIdx.x;
     const int hd = kv.head_dim, half = hd / 2, hkv = kv.n_kv_heads, bs = kv.block_size;
     const int nq = hq * half, nk = hkv * half, nv = hkv * hd;
@@ -155,16 +155,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const int width = (hq + 2 * hkv) * hd;
     const float *row = qkv + (int64_t)r * width;
     const int64_t zs = (int64_t)rows * width;   // distance between K slices
+    // perm: the weight rows of every q and k head were packed in the order the fused decode projection wants
+    // (qkv_packed_dim): dim j of a head then sits at column qkv_packed_dim(j) of the head
     auto val = [&](int c) {
         float v = row[c];
         for (int z = 1; z < S; ++z) v += row[z * zs + c];
         return v;
     };
+    auto qk_col = [&](int j) { return perm ? qkv_packed_dim(j, hd) : j; };
     const int slot = row_slot[r];
     const int pos = row_pos ? row_pos[r] : slot_len[slot];
     if (item < nq) {
         const int head = item / half, j = item % half;
-        const float x1 = val(head * hd + j), x2 = val(head * hd + j + half);
+        const float x1 = val(head * hd + qk_col(j)), x2 = val(head * hd + qk_col(j + half));
         const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
         T *qd = q_out + (int64_t)r * hq * hd + head * hd;
         qd[j] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
@@ -177,7 +180,7 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     if (item < nq + nk) {   // k heads -> K [tok][hd]
         const int i = item - nq, head = i / half, j = i % half;
         const int koff = hq * hd;
-        const float x1 = val(koff + head * hd + j), x2 = val(koff + head * hd + j + half);
+        const float x1 = val(koff + head * hd + qk_col(j)), x2 = val(koff + head * hd + qk_col(j + half));
         const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
         T *kd = pool + (int64_t)head * kv.head_elems() + (int64_t)tin * hd;
         kd[j] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
@@ -192,19 +195,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
 
 void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
-                        KvGeom kv, int layer, void *q_out, uint32_t *sat, hipStream_t s) {
+                        KvGeom kv, int layer, void *q_out, uint32_t *sat, int perm, hipStream_t s) {
     if (rows <= 0) return;
     const int items = hq * (kv.head_dim / 2) + kv.n_kv_heads * (kv.head_dim / 2) + kv.n_kv_heads * kv.head_dim;
     const dim3 grid(rows, (items + 255) / 256);
     if (dtype == KD_F32)
         rope_append_kernel<float><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                       layer, (float *)q_out, sat);
+                                                       layer, (float *)q_out, sat, perm);
     else if (dtype == KD_BF16)
         rope_append_kernel<bf16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                        layer, (bf16_t *)q_out, sat);
+                                                        layer, (bf16_t *)q_out, sat, perm);
     else
         rope_append_kernel<f16_t><<<grid, 256, 0, s>>>(qkv, S, rows, row_slot, row_pos, slot_len, rope_cos, rope_sin, hq, kv,
-                                                       layer, (f16_t *)q_out, sat);
+                                                       layer, (f16_t *)q_out, sat, perm);
 }
 
 // ------------------------------------------------------------------ bookkeeping
@@ -249,20 +252,23 @@ void launch_copy_block(int dtype, KvGeom kv, int n_layers, const int32_t *pairs,
 // TS: the caller's element type, TD: the kernel dtype of the copy (bf16 -> half is a value conversion)
 template <typename TS, typename TD> __device__ inline TD conv(TS v) { return from_f32<TD>(to_f32(v)); }
 
+// head_perm > 0: rows come in heads of head_perm rows, and row j of a head goes to row qkv_packed_dim(j) of it
 template <typename TS, typename TD>
-__global__ void pack_rows_kernel(const TS *__restrict__ src, TD *__restrict__ dst, int64_t cols, int64_t dst_row0) {
-    int64_t r = blockIdx.x;
-    for (int64_t i = threadIdx.x; i < cols; i += blockDim.x) dst[(dst_row0 + r) * cols + i] = conv<TS, TD>(src[r * cols + i]);
+__global__ void pack_rows_kernel(const TS *__restrict__ src, TD *__restrict__ dst, int64_t cols, int64_t dst_row0,
+                                 int head_perm) {
+    int64_t r = blockIdx.x, rd = r;
+    if (head_perm > 0) rd = (r / head_perm) * head_perm + qkv_packed_dim((int)(r % head_perm), head_perm);
+    for (int64_t i = threadIdx.x; i < cols; i += blockDim.x) dst[(dst_row0 + rd) * cols + i] = conv<TS, TD>(src[r * cols + i]);
 }
-void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
+void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0, int head_perm,
                       hipStream_t s) {
     if (rows <= 0) return;
     if (kd == KD_F32)
-        pack_rows_kernel<float, float><<<(unsigned)rows, 256, 0, s>>>((const float *)src, (float *)dst, cols, dst_row0);
+        pack_rows_kernel<float, float><<<(unsigned)rows, 256, 0, s>>>((const float *)src, (float *)dst, cols, dst_row0, head_perm);
     else if (kd == KD_BF16)
-        pack_rows_kernel<bf16_t, bf16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, cols, dst_row0);
+        pack_rows_kernel<bf16_t, bf16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (bf16_t *)dst, cols, dst_row0, head_perm);
     else
-        pack_rows_kernel<bf16_t, f16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (f16_t *)dst, cols, dst_row0);
+        pack_rows_kernel<bf16_t, f16_t><<<(unsigned)rows, 256, 0, s>>>((const bf16_t *)src, (f16_t *)dst, cols, dst_row0, head_perm);
 }
 
 // dst row 64t + c      = gate row 32t + c   (c < 32)

@@ -128,7 +128,9 @@ template <int N> __device__ inline void wait_vmcnt_le() {
 template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK, int EPI, bool M16 = false>
 __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__restrict__ A, const T *__restrict__ W,
                                                         void *__restrict__ Cv, int M, int N, int K, int mb, int nb,
-                                                        int S, int plain, uint32_t *__restrict__ sat) {
+                                                        int S, int plain, uint32_t *__restrict__ sat,
+                                                        GemmRowScale rsc) {
+    constexpr bool SWIGLU = (EPI == EPI_SWIGLU || EPI == EPI_SWIGLU_RS);
     constexpr int CPR = BK / 8;                           // 16-byte chunks per tile row
     constexpr int RPL = 64 / CPR;                         // tile rows one wave-wide load covers
     // rows that share a swizzle value (measured with a read-rate probe: 16-row fragment reads of 64-byte
@@ -145,7 +147,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     constexpr int STAGE_ELEMS = (BM + BN) * BK;
     static_assert(BK == 64 || BK == 32, "K tile");
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "whole passes");
-    static_assert(EPI != EPI_SWIGLU || (BN / WN) % 64 == 0, "SwiGLU needs whole 64-wide gate/up chunks per wave");
+    static_assert(!SWIGLU || (BN / WN) % 64 == 0, "SwiGLU needs whole 64-wide gate/up chunks per wave");
     static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     T *smem = (T *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
@@ -170,6 +172,11 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 
     const int tid = threadIdx.x, lane = tid % 64, wave = tid / 64;
     const int wm = wave / WN, wn = wave % WN;
+    // the rows' RMSNorm scale from the partial sums of squares ssq[tile][row]: two threads per row, every load of a
+    // thread in flight at once (a lane's neighbours read the neighbouring rows: whole cache lines per request)
+    constexpr int RS_MAXT = 24;                        // tiles one thread sums per round
+    __shared__ float s_rs[EPI == EPI_SWIGLU_RS ? BM : 1];
+    __shared__ float s_rs_part[EPI == EPI_SWIGLU_RS ? BM : 1];
     const int KT = K / BK;
     const int per = (KT + S - 1) / S;
     const int kt0 = z * per, kt1 = min(KT, kt0 + per);
@@ -283,6 +290,29 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     // tile kt lives in stage (kt - kt0) % NSTAGE; NSTAGE-1 tiles are in flight
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) issue_tile(kt0 + s, s);
+    // (behind the first tile loads, so that the pipeline is already filling while the statistics arrive; these are
+    // ordinary loads, younger than the tile loads: once they are back, so are the tiles)
+    if constexpr (EPI == EPI_SWIGLU_RS) {
+        static_assert(64 * WM * WN >= 2 * BM || EPI != EPI_SWIGLU_RS, "two threads per row");
+        const int r = tid % BM, part = tid / BM;       // part 0: even rounds of tiles, part 1: odd rounds
+        if (part < 2) {
+            const int row = min(m0 + r, M - 1);
+            float ss = 0.f;
+            for (int t0 = part * RS_MAXT; t0 < rsc.tiles; t0 += 2 * RS_MAXT) {
+                float v[RS_MAXT];
+#pragma unroll
+                for (int u = 0; u < RS_MAXT; ++u) v[u] = (t0 + u < rsc.tiles) ? rsc.ssq[(int64_t)(t0 + u) * M + row] : 0.f;
+#pragma unroll
+                for (int u = 0; u < RS_MAXT; ++u) ss += v[u];
+            }
+            if (part == 1) s_rs_part[r] = ss;
+            __syncthreads();
+            if (part == 0) s_rs[r] = 1.0f / sqrtf((ss + s_rs_part[r]) / (float)rsc.d + rsc.eps);
+        } else {
+            __syncthreads();
+        }
+        __syncthreads();
+    }
     int stage = 0;
     for (int kt = kt0; kt < kt1; ++kt) {
         wait_vmcnt_le<(NSTAGE - 2) * LOADS>();             // this thread's loads of tile kt have landed
@@ -304,7 +334,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int rbase = m0 + wm * (BM / WM) + i * 16 + row_l;
-            if (EPI == EPI_SWIGLU) {
+            if (SWIGLU) {
                 T *C = (T *)Cv;
 #pragma unroll
                 for (int p2 = 0; p2 < TN / 4; ++p2)            // a 64-wide chunk = tiles 4p2, 4p2+1 (gate), 4p2+2, 4p2+3 (up)
@@ -316,9 +346,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
                             for (int v = 0; v < 4; ++v) {
                                 const int row = rbase + v;
+                                const float sc = (EPI == EPI_SWIGLU_RS) ? s_rs[min(row - m0, BM - 1)] : 1.f;
                                 if (row < M)
-                                    C[(int64_t)row * (N / 2) + ocol] =
-                                        from_f32_sat<T>(silu_f(acc[i][4 * p2 + q][v]) * acc[i][4 * p2 + 2 + q][v], sat);
+                                    C[(int64_t)row * (N / 2) + ocol] = from_f32_sat<T>(
+                                        silu_f(acc[i][4 * p2 + q][v] * sc) * (acc[i][4 * p2 + 2 + q][v] * sc), sat);
                             }
                         }
                     }
@@ -345,7 +376,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int rbase = m0 + wm * (BM / WM) + i * 32 + row_l;
-        if (EPI == EPI_SWIGLU) {
+        if (SWIGLU) {
             T *C = (T *)Cv;
 #pragma unroll
             for (int p2 = 0; p2 < TN / 2; ++p2) {              // the wave's 64-wide chunks: 32 gate, 32 up columns
@@ -355,9 +386,10 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         int row = rbase + 8 * (v / 4) + (v % 4);
+                        const float sc = (EPI == EPI_SWIGLU_RS) ? s_rs[min(row - m0, BM - 1)] : 1.f;
                         if (row < M)
                             C[(int64_t)row * (N / 2) + ocol] =
-                                from_f32_sat<T>(silu_f(acc[i][2 * p2][v]) * acc[i][2 * p2 + 1][v], sat);
+                                from_f32_sat<T>(silu_f(acc[i][2 * p2][v] * sc) * (acc[i][2 * p2 + 1][v] * sc), sat);
                     }
                 }
             }
@@ -390,23 +422,32 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64, b
         set_attr<EPI_STORE_F32>();
         set_attr<EPI_RESID_F32>();
         set_attr<EPI_STORE_T>();
-        if constexpr (swiglu_ok) set_attr<EPI_SWIGLU>();
+        if constexpr (swiglu_ok) {
+            set_attr<EPI_SWIGLU>();
+            set_attr<EPI_SWIGLU_RS>();
+        }
     }
     // split > 1 only with EPI_STORE_F32, C then being the slice buffer [split][M][N]
-    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, int split, uint32_t *sat, hipStream_t s) {
+    static void run(const void *A, const void *W, void *C, int M, int N, int K, int epi, int split, uint32_t *sat, hipStream_t s,
+                    const GemmRowScale *row_scale = nullptr) {
+        const GemmRowScale rsc = row_scale ? *row_scale : GemmRowScale{nullptr, 0, 1, 0.f};
         const int mb = (M + BM - 1) / BM, nb = (N + BN - 1) / BN;
         const int units = nb * split;
         const int plain = (split == 1 && mb > 4) ? 1 : 0;
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
-            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain, sat); break;
-            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat); break;
+            case EPI_STORE_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, split, plain, sat, rsc); break;
+            case EPI_RESID_F32: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_RESID_F32, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat, rsc); break;
             case EPI_SWIGLU:
                 if constexpr (swiglu_ok)
-                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat);
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat, rsc);
                 break;
-            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat); break;
+            case EPI_SWIGLU_RS:
+                if constexpr (swiglu_ok)
+                    gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_SWIGLU_RS, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat, rsc);
+                break;
+            default: gemm_mfma_kernel<T, BM, BN, WM, WN, NSTAGE, BK, EPI_STORE_T, M16><<<grid, 64 * WM * WN, smem, s>>>(a, w, C, M, N, K, mb, nb, 1, plain, sat, rsc); break;
         }
     }
     // K slices so that the launch has about `want_blocks` blocks, each with >= 4 K tiles
@@ -441,10 +482,10 @@ void gemm_init() {
 
 template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
-                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s);
+                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s, const GemmRowScale *row_scale);
 
 int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s) {
+                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s, const GemmRowScale *row_scale) {
     if (M <= 0 || N <= 0) return 1;
     if (dtype == KD_F32) {
         gemm_simt<float>(A, W, C, M, N, K, epi, sat, s);
@@ -455,13 +496,13 @@ int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int 
         else gemm_simt<f16_t>(A, W, C, M, N, K, epi, sat, s);
         return 1;
     }
-    if (dtype == KD_BF16) return gemm_mfma_dispatch<bf16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s);
-    return gemm_mfma_dispatch<f16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s);
+    if (dtype == KD_BF16) return gemm_mfma_dispatch<bf16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s, row_scale);
+    return gemm_mfma_dispatch<f16_t>(A, W, C, M, N, K, epi, slices, slice_cap_floats, sat, s, row_scale);
 }
 
 template <typename T>
 static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int N, int K, int epi, float *slices,
-                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s) {
+                              size_t slice_cap_floats, uint32_t *sat, hipStream_t s, const GemmRowScale *row_scale) {
     // Configurations picked by measurement on MI355X (M = 256 decode rows / 16384 prefill rows, 1.5B shapes).
     typedef MfmaCfg<T, 256, 128, 4, 2, 3> CfgTall;          // 8 waves, wave tile 64x64, every decode row in one block
     // prefill: 16x16x32 products (measured +3 to +12 % over 32x32x16 at 16384 rows, nothing at decode sizes;
@@ -485,11 +526,11 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
     const int nb128 = (N + 127) / 128;
-    if (epi == EPI_SWIGLU || nb128 >= 96) {   // wide outputs: no K slices needed
-        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, sat, s);               // four 128-row blocks, three per CU at a time
-        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, sat, s);          // three 128-row blocks, not two of 256
-        else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, sat, s);   // a weight tile is fetched by exactly one block
-        else CfgLarge::run(A, W, C, M, N, K, epi, 1, sat, s);
+    if (epi == EPI_SWIGLU || epi == EPI_SWIGLU_RS || nb128 >= 96) {   // wide outputs: no K slices needed
+        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);       // four 128-row blocks, three per CU at a time
+        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);  // three 128-row blocks, not two of 256
+        else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);    // a weight tile is fetched by exactly one block
+        else CfgLarge::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);
         return 1;
     }
     if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the feed-forward down projection)

@@ -131,6 +131,14 @@ struct KvGeom {
     __host__ __device__ int64_t head_elems() const { return (int64_t)2 * block_size * head_dim; }
 };
 
+// Order of the weight rows (= output columns) of a q or k head for the fused decode projection: a 32-column
+// block holds 16 dims of the head's first half and, behind them, their 16 rotary partners (dim + hd/2), so
+// that a block can rotate what it computed.  Dim j of the head sits at column qkv_packed_dim(j).
+__host__ __device__ inline int qkv_packed_dim(int j, int hd) {
+    const int half = hd / 2;
+    return j < half ? 32 * (j / 16) + j % 16 : 32 * ((j - half) / 16) + 16 + j % 16;
+}
+
 // Epilogues of the projection GEMMs
 enum Epilogue {
     EPI_STORE_F32 = 0,   // C fp32 [M,N]
@@ -138,6 +146,15 @@ enum Epilogue {
     EPI_SWIGLU = 2,      // rows of W come in chunks of 64: 32 gate rows then the 32 matching up rows;
                          // C (model dtype) [M, N/2] = silu(gate) * up
     EPI_STORE_T = 3,     // C model dtype [M,N]
+    EPI_SWIGLU_RS = 4,   // EPI_SWIGLU on rows that carry the RMSNorm gain but not its scale: gate and up are
+                         // multiplied by the row's rsqrt(mean(h^2) + eps) first (statistics in GemmRowScale)
+};
+
+// Per-row RMSNorm statistics for EPI_SWIGLU_RS: ssq[t][row], t < tiles, are partial sums of squares of the row (as the fused output projection leaves them); scale = rsqrt(sum_t ssq / d + eps).
+struct GemmRowScale {
+    const float *ssq;
+    int tiles, d;
+    float eps;
 };
 
 // ---------------------------------------------------------------- kernel launchers
@@ -157,13 +174,24 @@ void gemm_init();   // once per process: raises the dynamic-LDS limit of the mat
 // EPI_RESID_F32, adds that sum to the residual stream).
 // `sat`: counter of half-range clamps of the epilogues that store activations (may be NULL).
 int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int M, int N, int K, int epi,
-                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s);
+                float *slices, size_t slice_cap_floats, uint32_t *sat, hipStream_t s,
+                const GemmRowScale *row_scale = nullptr);
+// Fused decode projections (gemm_skinny.hip); skinny_ok says whether the shape is one they take.
+bool skinny_ok(int M, int N, int K, int head_dim);
+void skinny_init();   // once per process, like gemm_init
+void launch_skinny_qkv(int dtype, const void *A, const void *W, int M, int K, const int32_t *row_slot,
+                       const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int hq, KvGeom kv, int layer,
+                       void *q_out, uint32_t *sat, hipStream_t s);
+// h += A W^T; h_act = (new h) * gain in the activation type (the next RMSNorm without its scale);
+// ssq[N/32][M]: partial sums of squares of the new rows
+void launch_skinny_o(int dtype, const void *A, const void *W, int M, int N, int K, float *h, const float *gain, void *h_act,
+                     float *ssq, uint32_t *sat, hipStream_t s);
 // Rotates q and k at each row's position, writes q (model dtype) and appends k, v to the cache.
 //   qkv fp32 [S][rows, (hq+2hkv)*hd] (S >= 1 K slices, summed here); row_slot [rows];
 //   row_pos [rows] or NULL (then pos = slot_len[slot])
 void launch_rope_append(int dtype, const float *qkv, int S, const int32_t *row_slot, const int32_t *row_pos,
                         const int32_t *slot_len, const float *rope_cos, const float *rope_sin, int rows, int hq,
-                        KvGeom kv, int layer, void *q_out, uint32_t *sat, hipStream_t s);
+                        KvGeom kv, int layer, void *q_out, uint32_t *sat, int perm, hipStream_t s);
 // Attention of each row's query heads over its slot's cache, positions 0..pos (plain ALU).
 void launch_attention_simt(int dtype, const void *q, const int32_t *row_slot, const int32_t *row_pos,
                            const int32_t *slot_len, int rows, int hq, KvGeom kv, int layer, void *out,
@@ -203,8 +231,10 @@ void launch_advantages(const float *rewards, const int32_t *off, int P, float ep
                        hipStream_t s);
 
 // weight repacking at context creation; the source has the model's dtype, the copy the kernel dtype `kd`
-void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0,
-                      hipStream_t s);   // dst[dst_row0 + r] = src[r]
+// dst[dst_row0 + r'] = src[r]; head_perm > 0: r' = r with its place inside its head of head_perm rows moved to
+// qkv_packed_dim
+void launch_pack_rows(int kd, const void *src, void *dst, int64_t rows, int64_t cols, int64_t dst_row0, int head_perm,
+                      hipStream_t s);
 void launch_pack_gate_up(int kd, const void *gate, const void *up, void *dst, int d_ff, int d, hipStream_t s);
 
 }  // namespace pc

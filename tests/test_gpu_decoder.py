@@ -406,3 +406,22 @@ def test_half_range_saturation_is_clamped_and_counted():
     assert np.isfinite(a["logits"]).all() and np.isfinite(a["last"]).all()
     b = _run_generate(BF, big, prompts, 2, 6, 5, dict(kw, act_dtype="bf16"))
     assert b["saturated"] == 0 and np.isfinite(b["logits"]).all()
+
+
+@pytest.mark.parametrize("model,lens", [(BF, [70, 33, 128, 5, 64]), (BF8, [100, 31])])
+def test_one_kernel_per_operation_decode_path(model, lens):
+    # PC_OPT_FUSE_DECODE = 0 keeps the unfused layer (projection, RoPE + append, RMSNorm as kernels of their own) for
+    # decode batches; it must match the oracle like the fused default, and the two must agree closely
+    import paper_2605_26606_amd as pc
+    say("decode layer with one kernel per operation, lens=%s" % lens)
+    w = workloads.perturb_norm_gains(workloads.make_weights(model, 3), 10)
+    toks, cu = workloads.make_ragged_prompts(lens, model.vocab, 8)
+    prompts = [toks[cu[i]:cu[i + 1]] for i in range(len(lens))]
+    kw = dict(block_size=64, kv_pool_bytes=512 << 20, max_slots=64, max_ctx=1024, max_batch_rows=1024)
+    a = _run_generate(model, w, prompts, 3, 12, 21, kw, opts=[(pc.PC_OPT_FUSE_DECODE, 0)])
+    _check(model, w, prompts, a, 21, 2e-2, range(0, len(lens) * 3, 2))
+    b = _run_generate(model, w, prompts, 3, 12, 21, kw)
+    # step 1 feeds both paths the same token wherever the first tokens agree (they come from the same prefill)
+    same0 = a["tokens"][:, 0] == b["tokens"][:, 0]
+    assert same0.all()
+    assert np.abs(a["logits"][1] - b["logits"][1]).max() <= 5e-3
