@@ -267,6 +267,21 @@ pc_status pc_select_commit(const float *p_hat, int32_t P, float p_lower, float p
                            int32_t b_t, uint8_t *cls, uint8_t *evict, int32_t *commit_idx,
                            int32_t *surplus_idx, int32_t *counts, void *stream);
 
+/* The pilot filter for rewards that are not binary (Introduction; Section 3.3: "applies to any scalar reward";
+ * Section 7 names the extension as open).  The paper gives no rule; this one selects on the pilot group's
+ * variance itself, with the asymmetry Section 3.3 argues for: a prompt whose mean reward has not passed
+ * mean_pivot is approaching the high-variance regime and needs var >= var_hard, one beyond it is leaving and
+ * needs var >= var_easy (>= var_hard in the paper's setting).
+ *   mean, var   device fp32 [P]: pilot mean and POPULATION variance, as pc_group_stats returns them
+ *   cls         0 too hard (not kept, mean <= mean_pivot), 1 keep, 2 too easy (not kept, mean > mean_pivot)
+ *   evict       mean >= mean_solve
+ *   everything else as in pc_select_commit.
+ * With 0/1 rewards, mean_pivot = 0.5, var_hard = p_lower (1 - p_lower), var_easy = p_upper (1 - p_upper) and
+ * p_lower <= 0.5 <= p_upper this is pc_select_commit's filter.  Comparisons are taken in fp32. */
+pc_status pc_select_commit_var(const float *mean, const float *var, int32_t P, float var_hard, float var_easy,
+                               float mean_pivot, float mean_solve, int32_t b_t, uint8_t *cls, uint8_t *evict,
+                               int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts, void *stream);
+
 /* Group-relative advantages A_i = (r_i - mu) / (sigma + eps) (Section 3.1,
  * Eq. 3), one group per kept prompt = its pilot and commit rollouts together
  * (Section 3.3 "Training").  A reward equal to the group mean gives exactly 0.

@@ -15,7 +15,7 @@ from .decoder import CachedDecoder
 
 
 def generate_group(model, w, prompt, prompt_uid, rollout_indices, new_tokens, temperature, seed,
-                   eos_id=-1, eos_logit_bias=0.0, dtype=np.float64, keep_logits=False):
+                   eos_id=-1, eos_logit_bias=0.0, dtype=np.float64, keep_logits=False, top_p=1.0):
     """Sample len(rollout_indices) completions of one prompt (Section 3.1).
 
     The prompt is run through the model once; every rollout continues from a
@@ -39,7 +39,7 @@ def generate_group(model, w, prompt, prompt_uid, rollout_indices, new_tokens, te
             if keep_logits:
                 seq_logits.append(np.asarray(logits, np.float32))
             u = philox.sampling_uniform(seed, uid, t)
-            tok, lp = sampler.sample_token(logits, temperature, u, eos_id, eos_logit_bias)
+            tok, lp = sampler.sample_token(logits, temperature, u, eos_id, eos_logit_bias, top_p)
             toks[a, t], lps[a, t] = tok, lp
             lens[a] = t + 1
             if tok == eos_id:
@@ -66,27 +66,32 @@ def pilot_commit_step(wl, w, prompts, prompt_uids, seed, eos_id=-1, eos_logit_bi
     Returns a dict with everything the step produces."""
     P = len(prompts)
     npil, ncom, T = wl.n_pilot, wl.n_commit, wl.new_tokens
+    top_p = getattr(wl, "top_p", 1.0)
     pilot_tok = np.full((P, npil, T), -1, np.int32)
     pilot_len = np.zeros((P, npil), np.int32)
     pilot_r = np.zeros((P, npil), np.float32)
     for q in range(P):
         t, l, _, _ = generate_group(wl.model, w, prompts[q], int(prompt_uids[q]), range(npil), T,
-                                    wl.temperature, seed, eos_id, eos_logit_bias, dtype)
+                                    wl.temperature, seed, eos_id, eos_logit_bias, dtype, top_p=top_p)
         pilot_tok[q], pilot_len[q] = t, l
         pilot_r[q] = score_group(wl.reward, t, l, int(prompt_uids[q]),
                                  None if p_q is None else p_q[q],
                                  None if reward_u is None else reward_u[q, :npil])
     off = np.arange(P + 1, dtype=np.int32) * npil
     n_pos, n_tot, p_hat, var = allocation.group_stats(pilot_r.reshape(-1), off)
-    cls, evict, commit_idx, surplus_idx, counts = allocation.select_commit(
-        p_hat, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t)
+    if getattr(wl, "filter", "binary") == "variance":
+        cls, evict, commit_idx, surplus_idx, counts = allocation.select_commit_variance(
+            p_hat, var, wl.var_hard, wl.var_easy, wl.mean_pivot, wl.p_solve, wl.b_t)
+    else:
+        cls, evict, commit_idx, surplus_idx, counts = allocation.select_commit(
+            p_hat, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t)
     K = len(commit_idx)
     commit_tok = np.full((K, ncom, T), -1, np.int32)
     commit_len = np.zeros((K, ncom), np.int32)
     commit_r = np.zeros((K, ncom), np.float32)
     for a, q in enumerate(commit_idx):
         t, l, _, _ = generate_group(wl.model, w, prompts[q], int(prompt_uids[q]), range(npil, npil + ncom), T,
-                                    wl.temperature, seed, eos_id, eos_logit_bias, dtype)
+                                    wl.temperature, seed, eos_id, eos_logit_bias, dtype, top_p=top_p)
         commit_tok[a], commit_len[a] = t, l
         commit_r[a] = score_group(wl.reward, t, l, int(prompt_uids[q]),
                                   None if p_q is None else p_q[q],

@@ -87,6 +87,7 @@ def library() -> C.CDLL:
             "pc_saturation_count": [vp, C.POINTER(i64), i32],
             "pc_group_stats": [vp, vp, i32, vp, vp, vp, vp, vp],
             "pc_select_commit": [vp, i32, f32, f32, f32, i32, vp, vp, vp, vp, vp, vp],
+            "pc_select_commit_var": [vp, vp, i32, f32, f32, f32, f32, i32, vp, vp, vp, vp, vp, vp],
             "pc_advantages": [vp, vp, i32, f32, vp, vp, vp, vp],
             "pc_sched_create": [C.POINTER(_SchedConfig), C.POINTER(vp)],
             "pc_sched_destroy": [vp],
@@ -333,6 +334,21 @@ def pc_select_commit(p_hat: torch.Tensor, P: int, p_lower: float, p_upper: float
                                       _dev(evict, torch.uint8, "evict"), _dev(commit_idx, torch.int32, "commit_idx"),
                                       _dev(surplus_idx, torch.int32, "surplus_idx"),
                                       _dev(counts, torch.int32, "counts"), _stream_ptr(stream)))
+
+
+def pc_select_commit_var(mean: torch.Tensor, var: torch.Tensor, P: int, var_hard: float, var_easy: float,
+                         mean_pivot: float, mean_solve: float, b_t: int, cls, evict, commit_idx, surplus_idx, counts,
+                         stream=None):
+    for t, name, need in ((mean, "mean", P), (var, "var", P), (cls, "cls", P), (evict, "evict", P),
+                          (commit_idx, "commit_idx", P), (surplus_idx, "surplus_idx", P), (counts, "counts", 4)):
+        if t is not None and t.numel() < need:
+            raise ValueError("%s too small" % name)
+    _check(library().pc_select_commit_var(_dev(mean, torch.float32, "mean"), _dev(var, torch.float32, "var"), int(P),
+                                          float(var_hard), float(var_easy), float(mean_pivot), float(mean_solve),
+                                          int(b_t), _dev(cls, torch.uint8, "cls"), _dev(evict, torch.uint8, "evict"),
+                                          _dev(commit_idx, torch.int32, "commit_idx"),
+                                          _dev(surplus_idx, torch.int32, "surplus_idx"),
+                                          _dev(counts, torch.int32, "counts"), _stream_ptr(stream)))
 
 
 def pc_advantages(rewards: torch.Tensor, group_off: torch.Tensor, eps: float, adv: torch.Tensor, mu=None, sigma=None,

@@ -47,8 +47,12 @@ void launch_group_stats(const float *rewards, const int32_t *off, int P, int32_t
 // One block walks the batch in chunks of 1024 prompts; the kept prompts are
 // compacted in batch order (ballot ranks inside a wave, a 16-entry prefix
 // across waves, a running count across chunks).
-__global__ __launch_bounds__(1024) void select_commit_kernel(const float *__restrict__ p_hat, int P, float lo, float hi,
-                                                             float solve, int b_t, uint8_t *__restrict__ cls,
+// VAR: the filter for rewards that are not binary: `p_hat` is the pilot mean, `var` the pilot variance, lo / hi are
+// the variance thresholds on the approaching (mean <= pivot) and on the leaving side (mean > pivot).
+template <bool VAR>
+__global__ __launch_bounds__(1024) void select_commit_kernel(const float *__restrict__ p_hat,
+                                                             const float *__restrict__ var, int P, float lo, float hi,
+                                                             float pivot, float solve, int b_t, uint8_t *__restrict__ cls,
                                                              uint8_t *__restrict__ evict,
                                                              int32_t *__restrict__ commit_idx,
                                                              int32_t *__restrict__ surplus_idx,
@@ -61,7 +65,14 @@ __global__ __launch_bounds__(1024) void select_commit_kernel(const float *__rest
         int c = -1;
         if (q < P) {
             const float ph = p_hat[q];
-            c = (ph > hi) ? 2 : (ph < lo) ? 0 : 1;
+            if (VAR) {
+                const float vr = var[q];
+                const bool approaching = ph <= pivot;
+                const bool kept = approaching ? (vr >= lo) : (vr >= hi);
+                c = kept ? 1 : (approaching ? 0 : 2);
+            } else {
+                c = (ph > hi) ? 2 : (ph < lo) ? 0 : 1;
+            }
             if (cls) cls[q] = (uint8_t)c;
             if (evict) evict[q] = (ph >= solve) ? 1 : 0;
         }
@@ -100,7 +111,15 @@ __global__ __launch_bounds__(1024) void select_commit_kernel(const float *__rest
 
 void launch_select_commit(const float *p_hat, int P, float lo, float hi, float solve, int b_t, uint8_t *cls,
                           uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts, hipStream_t s) {
-    select_commit_kernel<<<1, 1024, 0, s>>>(p_hat, P, lo, hi, solve, b_t, cls, evict, commit_idx, surplus_idx, counts);
+    select_commit_kernel<false><<<1, 1024, 0, s>>>(p_hat, nullptr, P, lo, hi, 0.f, solve, b_t, cls, evict, commit_idx,
+                                                   surplus_idx, counts);
+}
+
+void launch_select_commit_var(const float *mean, const float *var, int P, float var_hard, float var_easy, float pivot,
+                              float solve, int b_t, uint8_t *cls, uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx,
+                              int32_t *counts, hipStream_t s) {
+    select_commit_kernel<true><<<1, 1024, 0, s>>>(mean, var, P, var_hard, var_easy, pivot, solve, b_t, cls, evict,
+                                                  commit_idx, surplus_idx, counts);
 }
 
 // one thread per group, double inside

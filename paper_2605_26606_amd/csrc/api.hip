@@ -1117,6 +1117,19 @@ pc_status pc_select_commit(const float *p_hat, int32_t P, float p_lower, float p
     return check_launch();
 }
 
+pc_status pc_select_commit_var(const float *mean, const float *var, int32_t P, float var_hard, float var_easy,
+                               float mean_pivot, float mean_solve, int32_t b_t, uint8_t *cls, uint8_t *evict,
+                               int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts, void *stream) {
+    if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit_var: negative prompt count");
+    if (!counts || (P > 0 && (!mean || !var || !commit_idx))) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit_var: null argument");
+    if (!(var_hard >= 0.f) || !(var_easy >= 0.f))
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit_var: a variance threshold is negative or not a number");
+    if (b_t > 0 && !surplus_idx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_select_commit_var: a cap needs surplus_idx");
+    launch_select_commit_var(mean, var, P, var_hard, var_easy, mean_pivot, mean_solve, b_t, cls, evict, commit_idx,
+                             surplus_idx, counts, (hipStream_t)stream);
+    return check_launch();
+}
+
 pc_status pc_advantages(const float *rewards, const int32_t *group_off, int32_t P, float eps, float *adv, float *mu,
                         float *sigma, void *stream) {
     if (P < 0) PC_FAIL(PC_ERR_INVALID_ARG, "pc_advantages: negative group count");

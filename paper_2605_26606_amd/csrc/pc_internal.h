@@ -227,6 +227,9 @@ void launch_group_stats(const float *rewards, const int32_t *off, int P, int32_t
                         float *var, hipStream_t s);
 void launch_select_commit(const float *p_hat, int P, float lo, float hi, float solve, int b_t, uint8_t *cls,
                           uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx, int32_t *counts, hipStream_t s);
+void launch_select_commit_var(const float *mean, const float *var, int P, float var_hard, float var_easy, float pivot,
+                              float solve, int b_t, uint8_t *cls, uint8_t *evict, int32_t *commit_idx, int32_t *surplus_idx,
+                              int32_t *counts, hipStream_t s);
 void launch_advantages(const float *rewards, const int32_t *off, int P, float eps, float *adv, float *mu, float *sigma,
                        hipStream_t s);
 

@@ -7,6 +7,13 @@
 // (16 sub-segments, then an in-order wavefront scan), re-reading only that
 // segment.  Sums are accumulated in double so that the selected token agrees
 // with an in-order double-precision CDF except within rounding of a boundary.
+//
+// Nucleus truncation (top_p < 1): the tokens in order of decreasing probability (ties: lower id first) until their
+// cumulative mass reaches top_p keep their weight, the rest get none; the passes above then run on the kept
+// tokens.  Decreasing probability is decreasing logit, so the cut is found by a radix select over an
+// order-preserving 32-bit key of the logit, four passes of 8 bits, each with a histogram of the MASS per bucket
+// (double, one histogram per wave, added up in wave order): the bucket in which the cumulative mass from the top
+// crosses top_p * Z is the one to refine.  The row is re-read from L2 for every pass.
 #include "pc_internal.h"
 
 namespace pc {
@@ -40,9 +47,26 @@ __device__ inline float wave_max_f32(float v) {
     return v;
 }
 
+// order-preserving key of a float: a < b  <=>  okey(a) < okey(b)
+__device__ inline uint32_t okey(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// The kept set of a nucleus: logit key above kstar, or equal to it with an id up to tie_limit.
+struct Nucleus {
+    bool on;
+    uint32_t kstar;
+    int tie_limit;
+    float eos_key_add;   // the EOS bias in logit units (bias * temperature): the key of the EOS id is logit + this
+};
+__device__ inline uint32_t logit_key(float raw, int idx, int eos_id, float eos_key_add) {
+    return okey(idx == eos_id ? raw + eos_key_add : raw);
+}
+
 template <int VEC>
 __device__ inline void load_scaled(const float *__restrict__ x, int idx, int end, float inv_t, int eos_id,
-                                   float eos_bias, float (&v)[VEC], bool (&ok)[VEC]) {
+                                   float eos_bias, float (&v)[VEC], bool (&ok)[VEC], const Nucleus &nu) {
     if (VEC == 4 && idx + 3 < end) {
         const float4 t = *(const float4 *)(x + idx);
         v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
@@ -55,6 +79,13 @@ __device__ inline void load_scaled(const float *__restrict__ x, int idx, int end
             v[c] = ok[c] ? x[idx + c] : 0.f;
         }
     }
+    if (nu.on) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            const uint32_t key = logit_key(v[c], idx + c, eos_id, nu.eos_key_add);
+            ok[c] = ok[c] && (key > nu.kstar || (key == nu.kstar && idx + c <= nu.tie_limit));
+        }
+    }
 #pragma unroll
     for (int c = 0; c < VEC; ++c) {
         v[c] = v[c] * inv_t;
@@ -64,9 +95,10 @@ __device__ inline void load_scaled(const float *__restrict__ x, int idx, int end
 
 __device__ inline int round_up(int a, int b) { return (a + b - 1) / b * b; }
 
-template <int VEC>
+template <int VEC, bool TOPP>
 __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
-    const float *__restrict__ logits, const int32_t *__restrict__ logit_row, int vocab, float inv_t, uint64_t seed,
+    const float *__restrict__ logits, const int32_t *__restrict__ logit_row, int vocab, float inv_t, float top_p,
+    float eos_key_add, uint64_t seed,
     const uint64_t *__restrict__ seq_uid, const int32_t *__restrict__ step, int step_base, int eos_id, float eos_bias,
     int32_t *__restrict__ tokens_out, float *__restrict__ logprob_out, uint8_t *__restrict__ finished,
     int32_t *__restrict__ hist_tokens, float *__restrict__ hist_logprob, const int32_t *__restrict__ hist_index) {
@@ -94,9 +126,10 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
         s_u = ((float)(r[0] >> 9) + 0.5f) * (1.0f / 8388608.0f);   // exact in fp32, inside (0,1)
     }
     constexpr int STRIDE = WAVE * VEC;
+    Nucleus nu{false, 0u, 0x7fffffff, eos_key_add};
     // ---- level 1: online (max, sum) per contiguous wave segment
     const int seg = round_up((vocab + SAMPLE_WAVES - 1) / SAMPLE_WAVES, STRIDE);
-    {
+    auto level1 = [&]() {
         const int b = min(vocab, wave * seg), e = min(vocab, b + seg);
         float m = -INFINITY;
         double s = 0.0;
@@ -109,7 +142,7 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
             bool ok[AHEAD][VEC];
 #pragma unroll
             for (int u = 0; u < AHEAD; ++u)
-                load_scaled<VEC>(x, base + u * STRIDE + lane * VEC, e, inv_t, eos_id, eos_bias, v[u], ok[u]);
+                load_scaled<VEC>(x, base + u * STRIDE + lane * VEC, e, inv_t, eos_id, eos_bias, v[u], ok[u], nu);
 #pragma unroll
             for (int u = 0; u < AHEAD; ++u) {
                 float lm = -INFINITY;
@@ -131,6 +164,128 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
             s_wm[wave] = wm;
             s_ws[wave] = ws;
         }
+    };
+    level1();
+    if constexpr (TOPP) {
+        // ---- nucleus: the key kstar and the id limit among its ties at which the mass from the top reaches top_p Z
+        __shared__ double s_hist[SAMPLE_WAVES][256];
+        __shared__ int s_cnt[SAMPLE_WAVES][256];
+        __shared__ double s_comb[256];
+        __shared__ int s_ccnt[256];
+        __shared__ uint32_t s_prefix;
+        __shared__ double s_above;
+        __shared__ int s_keep_ties, s_tie_limit, s_wcount[SAMPLE_WAVES];
+        __syncthreads();
+        float M0 = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < SAMPLE_WAVES; ++w) M0 = fmaxf(M0, s_wm[w]);
+        double Z0 = 0.0;
+#pragma unroll
+        for (int w = 0; w < SAMPLE_WAVES; ++w) Z0 += (s_wm[w] == -INFINITY) ? 0.0 : s_ws[w] * (double)expf(s_wm[w] - M0);
+        const double want = (double)top_p * Z0;
+        if (tid == 0) {
+            s_prefix = 0u;
+            s_above = 0.0;
+        }
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            for (int bkt = lane; bkt < 256; bkt += WAVE) {
+                s_hist[wave][bkt] = 0.0;
+                s_cnt[wave][bkt] = 0;
+            }
+            __syncthreads();
+            const uint32_t prefix = s_prefix;
+            for (int base = tid * VEC; base < vocab; base += SAMPLE_WAVES * WAVE * VEC) {
+                float v[VEC];
+                bool ok[VEC];
+                float raw[VEC];
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) raw[c] = (base + c < vocab) ? x[base + c] : 0.f;
+                load_scaled<VEC>(x, base, vocab, inv_t, eos_id, eos_bias, v, ok, nu);
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    if (!ok[c]) continue;
+                    const uint32_t key = logit_key(raw[c], base + c, eos_id, eos_key_add);
+                    if (pass > 0 && (key >> (shift + 8)) != prefix) continue;
+                    const int bkt = (key >> shift) & 255;
+                    atomicAdd(&s_hist[wave][bkt], (double)expf(v[c] - M0));
+                    atomicAdd(&s_cnt[wave][bkt], 1);
+                }
+            }
+            __syncthreads();
+            if (tid < 256) {   // the waves' histograms in wave order
+                double h = 0.0;
+                int cn = 0;
+#pragma unroll
+                for (int w = 0; w < SAMPLE_WAVES; ++w) {
+                    h += s_hist[w][tid];
+                    cn += s_cnt[w][tid];
+                }
+                s_comb[tid] = h;
+                s_ccnt[tid] = cn;
+            }
+            __syncthreads();
+            if (tid == 0) {   // from the top bucket down: where the cumulative mass reaches the wanted one
+                double run = s_above;
+                int sel = -1, lowest = 0;
+                for (int bkt = 255; bkt >= 0; --bkt) {
+                    if (s_ccnt[bkt] == 0) continue;
+                    lowest = bkt;
+                    if (run + s_comb[bkt] >= want) {
+                        sel = bkt;
+                        break;
+                    }
+                    run += s_comb[bkt];
+                }
+                if (sel < 0) {   // rounding left the total short of top_p Z: every token stays
+                    sel = lowest;
+                    run -= s_comb[lowest];
+                }
+                s_above = run;
+                s_prefix = (prefix << 8) | (uint32_t)sel;
+                if (pass == 3) {   // ties at the cut: as many as it takes, lowest ids first
+                    const int c = s_ccnt[sel];
+                    const double wt = s_comb[sel] / (double)c;
+                    int r = (int)ceil((want - run) / wt);
+                    r = max(1, min(r, c));
+                    while (r > 1 && run + (double)(r - 1) * wt >= want) --r;
+                    while (r < c && run + (double)r * wt < want) ++r;
+                    s_keep_ties = (r >= c) ? -1 : r;
+                }
+            }
+            __syncthreads();
+        }
+        nu.kstar = s_prefix;
+        nu.tie_limit = 0x7fffffff;
+        const int keep_ties = s_keep_ties;
+        if (keep_ties > 0) {   // (block-uniform, rare) only the first keep_ties of the tied ids stay: find the id of the last one
+            int seen = 0;      // ties in the ids before this chunk (same value in every thread)
+            int limit = -1;
+            for (int base = 0; base < vocab && limit < 0; base += SAMPLE_WAVES * WAVE) {
+                const int idx = base + tid;
+                const bool tie = idx < vocab && logit_key(x[idx], idx, eos_id, eos_key_add) == nu.kstar;
+                const unsigned long long bal = __ballot(tie);
+                if (lane == 0) s_wcount[wave] = __popcll(bal);
+                __syncthreads();
+                int before = 0, total = 0;
+#pragma unroll
+                for (int w = 0; w < SAMPLE_WAVES; ++w) {
+                    if (w < wave) before += s_wcount[w];
+                    total += s_wcount[w];
+                }
+                if (seen + total >= keep_ties) {   // the last kept tie is in this chunk
+                    const int rank = seen + before + __popcll(bal & ((1ull << lane) - 1ull));   // ties before this id
+                    if (tie && rank == keep_ties - 1) s_tie_limit = idx;
+                    limit = 0;
+                }
+                seen += total;
+                __syncthreads();
+            }
+            nu.tie_limit = s_tie_limit;
+        }
+        nu.on = true;
+        __syncthreads();
+        level1();   // the same pass over the kept tokens only
     }
     __syncthreads();
     float M = -INFINITY;
@@ -174,7 +329,7 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
         for (int base = b; base < e; base += STRIDE) {
             float v[VEC];
             bool ok[VEC];
-            load_scaled<VEC>(x, base + lane * VEC, e, inv_t, eos_id, eos_bias, v, ok);
+            load_scaled<VEC>(x, base + lane * VEC, e, inv_t, eos_id, eos_bias, v, ok, nu);
 #pragma unroll
             for (int c = 0; c < VEC; ++c)
                 if (ok[c]) s += (double)expf(v[c] - M);
@@ -218,7 +373,7 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void sample_kernel(
         float v[VEC];
         bool ok[VEC];
         const int idx = base + lane * VEC;
-        load_scaled<VEC>(x, idx, je, inv_t, eos_id, eos_bias, v, ok);
+        load_scaled<VEC>(x, idx, je, inv_t, eos_id, eos_bias, v, ok, nu);
         double pre[VEC], lsum = 0.0;
         int my_last = -1;
 #pragma unroll
@@ -279,14 +434,19 @@ void launch_sample(const float *logits, const int32_t *logit_row, int n, int voc
     if (n <= 0) return;
     const float inv_t = 1.0f / temperature;
     const bool vec = (vocab % 4 == 0) && (((uintptr_t)logits) % 16 == 0);
-    if (vec)
-        sample_kernel<4><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
-                                                           step_base, eos_id, eos_bias, tokens_out, logprob_out,
-                                                           finished, hist_tokens, hist_logprob, hist_index);
-    else
-        sample_kernel<1><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, seed, seq_uid, step,
-                                                           step_base, eos_id, eos_bias, tokens_out, logprob_out,
-                                                           finished, hist_tokens, hist_logprob, hist_index);
+    const float key_add = (eos_id >= 0) ? eos_bias * temperature : 0.f;
+#define PC_SAMPLE(V, TP)                                                                                          \
+    sample_kernel<V, TP><<<n, SAMPLE_WAVES * WAVE, 0, s>>>(logits, logit_row, vocab, inv_t, top_p, key_add, seed, seq_uid, \
+                                                           step, step_base, eos_id, eos_bias, tokens_out, logprob_out,      \
+                                                           finished, hist_tokens, hist_logprob, hist_index)
+    if (top_p < 1.0f) {
+        if (vec) PC_SAMPLE(4, true);
+        else PC_SAMPLE(1, true);
+    } else {
+        if (vec) PC_SAMPLE(4, false);
+        else PC_SAMPLE(1, false);
+    }
+#undef PC_SAMPLE
 }
 
 // log softmax(logits / T) at a given token per row (teacher-forced scoring: Section 3.1, the per-token
@@ -308,7 +468,7 @@ __global__ __launch_bounds__(SAMPLE_WAVES *WAVE) void logprob_kernel(const float
     for (int base = tid * VEC; base < vocab; base += SAMPLE_WAVES * WAVE * VEC) {
         float v[VEC];
         bool ok[VEC];
-        load_scaled<VEC>(x, base, vocab, inv_t, -1, 0.f, v, ok);
+        load_scaled<VEC>(x, base, vocab, inv_t, -1, 0.f, v, ok, Nucleus{false, 0u, 0, 0.f});
         float lm = -INFINITY;
 #pragma unroll
         for (int c = 0; c < VEC; ++c)

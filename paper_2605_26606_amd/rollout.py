@@ -143,6 +143,10 @@ def synthetic_rewards(rule: str, tokens: torch.Tensor, lengths: torch.Tensor, pr
         r = (last % 7 == prompt_uid_per_seq.long() % 7)
     elif rule == "bernoulli":
         r = reward_u < p_q_per_seq
+    elif rule == "graded_mod7":
+        d = (last - prompt_uid_per_seq.long()) % 7
+        d = torch.minimum(d, 7 - d)
+        return (3 - d).to(torch.float32) / 3.0
     else:
         raise ValueError(rule)
     return r.to(torch.float32)
@@ -186,8 +190,9 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     tkw = dict(time_class=time_class, time_every=time_every)
     ts_p = [] if timed_steps is not None else None
     ts_c = [] if timed_steps is not None else None
+    top_p = float(getattr(wl, "top_p", 1.0))
     g = generate(ctx, handles[rows], rows, last_logits, _seq_uids(uids, range(npil)), T, wl.temperature, seed,
-                 eos_id, eos_logit_bias, stream, timed_steps=ts_p, **tkw)
+                 eos_id, eos_logit_bias, stream, timed_steps=ts_p, top_p=top_p, **tkw)
     mark()
     rows_d = torch.from_numpy(rows).to(dev).long()
     pilot_r = synthetic_rewards(wl.reward, g["tokens"], g["lengths"], uid_d[rows_d],
@@ -204,8 +209,12 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     commit_idx = torch.empty(P, dtype=torch.int32, device=dev)
     surplus_idx = torch.empty(P, dtype=torch.int32, device=dev)
     counts = torch.empty(4, dtype=torch.int32, device=dev)
-    B.pc_select_commit(p_hat, P, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t, cls, evict, commit_idx, surplus_idx,
-                       counts, stream)
+    if getattr(wl, "filter", "binary") == "variance":
+        B.pc_select_commit_var(p_hat, var, P, wl.var_hard, wl.var_easy, wl.mean_pivot, wl.p_solve, wl.b_t, cls, evict,
+                               commit_idx, surplus_idx, counts, stream)
+    else:
+        B.pc_select_commit(p_hat, P, wl.p_lower, wl.p_upper, wl.p_solve, wl.b_t, cls, evict, commit_idx, surplus_idx,
+                           counts, stream)
     counts_h = counts.cpu().numpy()            # the one read-back the method needs: the commit pass's size
     K = int(counts_h[0])
     kept = commit_idx[:K].cpu().numpy()
@@ -215,7 +224,7 @@ def pilot_commit_step(ctx: B.Context, wl, prompt_tokens: torch.Tensor, cu_lens: 
     mark()
     crow = np.repeat(kept.astype(np.int32), ncom)
     gc = generate(ctx, handles[crow], crow, last_logits, _seq_uids(uids[kept], range(npil, npil + ncom)), T,
-                  wl.temperature, seed, eos_id, eos_logit_bias, stream, timed_steps=ts_c)   # timing: pilot pass only
+                  wl.temperature, seed, eos_id, eos_logit_bias, stream, timed_steps=ts_c, top_p=top_p)   # timing: pilot pass only
     if timed_steps is not None:
         # (pass, step, sequences, prompts whose prefix those sequences share)
         timed_steps.extend(("pilot", t, n, P) for t, n in ts_p)

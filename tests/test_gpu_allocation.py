@@ -126,3 +126,59 @@ def test_advantages_match_oracle(sizes):
     wadv, _, _ = al.advantages(r, off, 1e-6)
     got = adv.cpu().numpy()
     assert np.abs(got - wadv).max() <= 2.4e-7 * max(1.0, np.abs(wadv).max())
+
+
+def test_variance_filter_bit_exact():
+    # pc_select_commit_var against the oracle's reading for rewards that are not binary: multi-valued rewards, all
+    # three classes, caps, thresholds hit exactly; and, on 0/1 rewards with thresholds p (1 - p), the same output as
+    # pc_select_commit (Section 4.2 thresholds)
+    import paper_2605_26606_amd as pc
+    d = "cuda"
+    rng = np.random.default_rng(12)
+    for P, G, levels, b_t in ((64, 4, 3, 0), (1000, 8, 5, 100), (5000, 16, 11, 0), (3, 4, 2, 1), (1, 4, 3, 0)):
+        r = (rng.integers(0, levels, P * G) / float(levels - 1)).astype(np.float32)
+        r.reshape(P, G)[: P // 4] = np.round(r.reshape(P, G)[: P // 4])          # some binary groups
+        off = (np.arange(P + 1) * G).astype(np.int32)
+        mean = torch.empty(P, device=d)
+        var = torch.empty(P, device=d)
+        pc.pc_group_stats(torch.from_numpy(r).to(d), torch.from_numpy(off).to(d), None, None, mean, var)
+        _, _, wmean, wvar = al.group_stats(r, off)
+        assert np.array_equal(mean.cpu().numpy(), wmean)
+        assert np.abs(var.cpu().numpy() - wvar).max() <= 1e-7
+        mean_h, var_h = mean.cpu().numpy(), var.cpu().numpy()
+        for vh, ve, pv, so in ((0.109375, 0.1875, 0.5, 1.0), (0.05, 0.05, 0.4, 0.8), (0.0, 0.3, 0.5, 2.0)):
+            cls = torch.full((P,), 9, dtype=torch.uint8, device=d)
+            ev = torch.full((P,), 9, dtype=torch.uint8, device=d)
+            ci = torch.full((P,), -1, dtype=torch.int32, device=d)
+            si = torch.full((P,), -1, dtype=torch.int32, device=d)
+            cnt = torch.zeros(4, dtype=torch.int32, device=d)
+            pc.pc_select_commit_var(mean, var, P, vh, ve, pv, so, b_t, cls, ev, ci, si, cnt)
+            torch.cuda.synchronize()
+            wcls, wev, wci, wsi, wcnt = al.select_commit_variance(mean_h, var_h, vh, ve, pv, so, b_t)
+            assert np.array_equal(cls.cpu().numpy(), wcls) and np.array_equal(ev.cpu().numpy(), wev)
+            assert np.array_equal(cnt.cpu().numpy(), wcnt)
+            assert np.array_equal(ci.cpu().numpy()[:wcnt[0]], wci) and (ci.cpu().numpy()[wcnt[0]:] == -1).all()
+            assert np.array_equal(si.cpu().numpy()[:wcnt[1]], wsi) and (si.cpu().numpy()[wcnt[1]:] == -1).all()
+    # binary truth table through both entry points
+    for n in (4, 8, 16, 32):
+        groups = np.concatenate([np.r_[np.ones(k, np.float32), np.zeros(n - k, np.float32)] for k in range(n + 1)])
+        off = (np.arange(n + 2) * n).astype(np.int32)
+        P = n + 1
+        mean = torch.empty(P, device=d)
+        var = torch.empty(P, device=d)
+        pc.pc_group_stats(torch.from_numpy(groups).to(d), torch.from_numpy(off).to(d), None, None, mean, var)
+        outs = []
+        for which in ("binary", "variance"):
+            cls = torch.empty(P, dtype=torch.uint8, device=d)
+            ev = torch.empty(P, dtype=torch.uint8, device=d)
+            ci = torch.full((P,), -1, dtype=torch.int32, device=d)
+            si = torch.full((P,), -1, dtype=torch.int32, device=d)
+            cnt = torch.zeros(4, dtype=torch.int32, device=d)
+            if which == "binary":
+                pc.pc_select_commit(mean, P, 0.125, 0.75, 1.0, 3, cls, ev, ci, si, cnt)
+            else:
+                pc.pc_select_commit_var(mean, var, P, 0.125 * 0.875, 0.75 * 0.25, 0.5, 1.0, 3, cls, ev, ci, si, cnt)
+            torch.cuda.synchronize()
+            outs.append([t.cpu().numpy() for t in (cls, ev, ci, si, cnt)])
+        for a, b in zip(*outs):
+            assert np.array_equal(a, b)

@@ -300,3 +300,50 @@ def test_bound_pipeline_16bit_against_the_oracle():
         assert np.array_equal(nxt["advantages"].cpu().numpy().reshape(-1), adv)
     say("bound pipeline, 16-bit: %d/%d tokens from the oracle's own logits" % (ok, tot))
     assert tot >= 600 and ok >= math.ceil(0.99 * tot)
+
+
+def test_step_with_top_p_and_variance_filter_matches_oracle():
+    # evaluation-style sampling (temperature 0.7, top_p 0.9) with a four-valued reward and the variance filter
+    # (the reading for rewards that are not binary): whole step on the fp32 model against the oracle
+    wl = workloads.scaled(workloads.WORKLOADS["C1"], temperature=0.7, top_p=0.9, reward="graded_mod7", filter="variance",
+                          var_hard=0.02, var_easy=0.05, n_prompts=12, new_tokens=8)
+    say("whole step with top-p sampling, graded rewards, variance filter")
+    w = workloads.make_weights(wl.model, wl.seed_weights)
+    prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, wl.model.vocab, wl.seed_prompts)
+    uids = workloads.make_prompt_uids(wl.n_prompts, first=40)
+    got = _step(wl, w, prompts, uids, wl.seed_sampler, block_size=32, kv_pool_bytes=64 << 20, max_slots=256,
+                max_ctx=64, max_batch_rows=512)
+    want = orollout.pilot_commit_step(wl, w, prompts, uids, wl.seed_sampler)
+    same = np.array_equal(got["pilot_tokens"], want["pilot_tokens"])
+    say("free-running pilot tokens identical: %s" % same)
+    # teacher-forced in any case: the oracle's top-p sampler on its own logits reproduces the GPU's tokens
+    ok = tot = 0
+    for q in range(wl.n_prompts):
+        for j in range(wl.n_pilot):
+            seq = np.concatenate([prompts[q], got["pilot_tokens"][q, j]])
+            lg = decoder.forward_full(wl.model, w, seq[:-1], rows=np.arange(wl.prompt_len - 1, len(seq) - 1))
+            for t in range(wl.new_tokens):
+                u = philox.sampling_uniform(wl.seed_sampler, philox.seq_uid(uids[q], j), t)
+                ok += int(sampler.sample_token(lg[t], 0.7, u, top_p=0.9)[0] == got["pilot_tokens"][q, j, t])
+                tot += 1
+    assert ok >= math.ceil(0.995 * tot)
+    # rewards follow the rule; statistics, variance filter, commit set and advantages follow the rewards bit-exactly
+    d = (got["pilot_tokens"][:, :, -1].astype(np.int64) - uids[:, None]) % 7
+    d = np.minimum(d, 7 - d)
+    assert np.array_equal(got["pilot_rewards"], ((3 - d).astype(np.float32) / np.float32(3.0)))
+    P, npil, ncom = wl.n_prompts, wl.n_pilot, wl.n_commit
+    off = (np.arange(P + 1) * npil).astype(np.int32)
+    n_pos, n_tot, mean, var = allocation.group_stats(got["pilot_rewards"].reshape(-1), off)
+    assert np.array_equal(got["p_hat"], mean) and np.abs(got["var"] - var).max() <= 1e-7
+    cls, evict, commit, surplus, counts = allocation.select_commit_variance(got["p_hat"], got["var"], wl.var_hard,
+                                                                            wl.var_easy, wl.mean_pivot, wl.p_solve, 0)
+    assert np.array_equal(got["cls"], cls) and np.array_equal(got["evict"], evict)
+    assert np.array_equal(got["commit_idx"], commit) and np.array_equal(got["counts"], counts)
+    assert 0 < counts[0] < P                    # the filter keeps some prompts and drops some
+    K = len(commit)
+    union = np.concatenate([got["pilot_rewards"][commit], got["commit_rewards"]], axis=1)
+    assert np.array_equal(got["union_rewards"], union)
+    adv, mu, sigma = allocation.advantages(union.reshape(-1), (np.arange(K + 1) * (npil + ncom)).astype(np.int32))
+    assert np.abs(got["advantages"].reshape(-1) - adv).max() <= 5e-7
+    if same and np.array_equal(got["commit_idx"], want["commit_idx"]):
+        assert np.array_equal(got["commit_tokens"], want["commit_tokens"])

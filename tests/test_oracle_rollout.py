@@ -112,3 +112,42 @@ def test_reward_rules_worked_examples():
     assert got.tolist() == [0.0, 1.0]
     got = rollout.score_group("last_mod7", toks, np.array([3, 4]), prompt_uid=9)   # 9 = 7 + 2; 9 mod 7 = 2, 6 mod 7 = 6
     assert got.tolist() == [1.0, 0.0]
+
+
+def test_graded_reward_worked_examples():
+    # residues of the last token and of the prompt uid on the circle mod 7: distance 0, 1, 2, 3 -> 1, 2/3, 1/3, 0
+    #   14 vs 0: both residue 0;  15 vs 0: 1 apart;  20 (= 2*7 + 6) vs 0: 1 apart the other way round;
+    #   16 vs 0: 2;  17 vs 0: 3;  18 (residue 4) vs 0: 3;  19 (residue 5) vs 0: 2;  3 vs 10 (residue 3): 0
+    for tok, uid, want in ((14, 0, 1.0), (15, 0, 2 / 3), (20, 0, 2 / 3), (16, 0, 1 / 3), (17, 0, 0.0), (18, 0, 0.0),
+                           (19, 0, 1 / 3), (3, 10, 1.0), (0, 6, 2 / 3), (151935, 13, 2 / 3)):
+        got = rewards.reward("graded_mod7", last_tok=tok, prompt_uid=uid)
+        assert abs(got - want) < 1e-7, (tok, uid, got, want)
+    vals = {rewards.reward("graded_mod7", last_tok=t, prompt_uid=5) for t in range(70)}
+    assert len(vals) == 4 and min(vals) == 0.0 and max(vals) == 1.0
+
+
+def test_step_with_top_p_and_the_variance_filter():
+    # the step's wiring with evaluation-style sampling (temperature 0.7, top_p 0.9) and a four-valued reward
+    # selected on by the variance filter
+    wl = workloads.scaled(WL, temperature=0.7, top_p=0.9, reward="graded_mod7", filter="variance", var_hard=0.02,
+                          var_easy=0.05, n_prompts=6, new_tokens=6)
+    w, prompts, uids = _setup()
+    prompts, uids = prompts[:6], uids[:6]
+    out = rollout.pilot_commit_step(wl, w, prompts, uids, 3)
+    # a token is always inside the nucleus of its own logits, and is the top-p sampler's choice
+    q, j = 2, 1
+    seq = np.concatenate([prompts[q], out["pilot_tokens"][q, j]])
+    logits = decoder.forward_full(wl.model, w, seq[:-1])
+    for t in range(wl.new_tokens):
+        lg = logits[wl.prompt_len - 1 + t]
+        u = philox.sampling_uniform(3, philox.seq_uid(uids[q], j), t)
+        assert sampler.sample_token(lg, 0.7, u, top_p=0.9)[0] == out["pilot_tokens"][q, j, t]
+        x = np.asarray(lg, np.float32).astype(np.float64) / 0.7
+        assert sampler.nucleus(np.exp(x - x.max()), 0.9)[out["pilot_tokens"][q, j, t]]
+    want_r = np.array([[rewards.reward("graded_mod7", last_tok=int(t[-1]), prompt_uid=int(uids[a])) for t in row]
+                       for a, row in enumerate(out["pilot_tokens"])], np.float32)
+    assert np.array_equal(out["pilot_rewards"], want_r)
+    mean, var = want_r.astype(np.float64).mean(1), want_r.astype(np.float64).var(1)
+    kept = [a for a in range(6) if (var[a] >= 0.02 - 1e-9 if mean[a] <= 0.5 else var[a] >= 0.05 - 1e-9)]
+    assert list(out["commit_idx"]) == kept
+    assert out["union_rewards"].shape == (len(kept), 8)

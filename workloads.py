@@ -68,7 +68,12 @@ class Workload:
     n_commit: int
     new_tokens: int
     temperature: float = 1.0
-    reward: str = "last_even"    # "last_even" | "last_mod7" | "bernoulli"
+    top_p: float = 1.0           # nucleus sampling (1.0 = off: the paper's training setting, Section 4.2)
+    reward: str = "last_even"    # "last_even" | "last_mod7" | "bernoulli" | "graded_mod7" (four-valued)
+    filter: str = "binary"       # "binary": p_lower <= p_hat <= p_upper; "variance": on the pilot variance
+    var_hard: float = 0.109375   # variance filter: threshold while the mean is <= mean_pivot (0.125 * 0.875)
+    var_easy: float = 0.1875     #                  threshold beyond it (0.75 * 0.25)
+    mean_pivot: float = 0.5
     eos: bool = False            # per-sequence early stop at a seeded EOS id
     p_lower: float = 0.125       # Section 4.2 thresholds
     p_upper: float = 0.75
@@ -92,6 +97,10 @@ WORKLOADS: Dict[str, Workload] = {
     "C3": Workload("C3", _QWEN15, 128, 512, 8, 8, 2048, reward="last_mod7", eos=True),
     "C4": Workload("C4", _QWEN8, 64, 512, 4, 12, 2048, reward="bernoulli"),
     "C5": Workload("C5", _QWEN14, 32, 1024, 4, 12, 4096, reward="bernoulli", eos=True),
+    # the 1.5B stress shape with the paper's evaluation sampling (Section 4.2: temperature 0.7; top-p is this
+    # build's addition: 0.95) and a four-valued reward selected on by the variance filter
+    "C3E": Workload("C3E", _QWEN15, 128, 512, 8, 8, 2048, temperature=0.7, top_p=0.95, reward="graded_mod7",
+                    filter="variance", var_hard=0.02, var_easy=0.05, eos=True),
 }
 
 
