@@ -66,24 +66,89 @@ def attention_bytes_per_launch(model, n_prompts_active, prompt_len, n_seqs, t):
 
 
 def cpu_baseline(wl, w_dev, prompts, uids, seed):
-    """Times the oracle, as it stands, on a bounded sample of the same workload."""
+    """Times the oracle, as it stands, on bounded samples of the same workload: prefill and decode separately, with
+    all host threads and with one."""
     import numpy as np
     import torch
-    from oracle import rollout as orollout
+    from oracle import philox, sampler
+    from oracle.decoder import CachedDecoder
     try:
-        from threadpoolctl import threadpool_info
+        from threadpoolctl import threadpool_info, threadpool_limits
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [torch.get_num_threads()])
     except Exception:
+        threadpool_limits = None
         threads = torch.get_num_threads()
     w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w_dev.items()}
+
+    def run(n_prefill, n_roll, n_new):
+        t0 = time.perf_counter()
+        base = CachedDecoder(wl.model, w_cpu)
+        first = base.extend(prompts[0][:n_prefill])
+        t1 = time.perf_counter()
+        for j in range(n_roll):
+            dec, logits = base.clone(), first
+            uid = philox.seq_uid(int(uids[0]), j)
+            for t in range(n_new):
+                tok, _ = sampler.sample_token(logits, wl.temperature, philox.sampling_uniform(seed, uid, t))
+                logits = dec.extend([tok])          # n_new decode forwards per rollout
+        t2 = time.perf_counter()
+        return n_prefill / (t1 - t0), n_roll * n_new / (t2 - t1), n_roll * n_new / (t2 - t0), t2 - t0
+
     n_roll, n_new = 2, 4
-    t0 = time.perf_counter()
-    toks, lens, _, _ = orollout.generate_group(wl.model, w_cpu, prompts[0], int(uids[0]), range(n_roll), n_new,
-                                               wl.temperature, seed)
-    dt = time.perf_counter() - t0
-    return {"value": float(lens.sum()) / dt, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": "1 prompt x %d tokens prefilled once, %d rollouts x %d new tokens, float64 numpy (%.1f s)"
-                      % (wl.prompt_len, n_roll, n_new, dt)}
+    pre, dec, both, secs = run(wl.prompt_len, n_roll, n_new)
+    out = {"value": both, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+           "sample": "1 prompt x %d tokens prefilled once, %d rollouts x %d decode forwards, float64 numpy (%.1f s); value "
+                     "= generated tokens / (prefill + decode) time" % (wl.prompt_len, n_roll, n_new, secs),
+           "prefill_tokens_per_s": round(pre, 2), "decode_tokens_per_s": round(dec, 3)}
+    if threadpool_limits is not None:
+        with threadpool_limits(limits=1):
+            torch_threads = torch.get_num_threads()
+            torch.set_num_threads(1)
+            pre1, dec1, _, secs1 = run(32, 1, 2)
+            torch.set_num_threads(torch_threads)
+        out["one_thread"] = {"prefill_tokens_per_s": round(pre1, 2), "decode_tokens_per_s": round(dec1, 3),
+                             "sample": "32 prompt tokens, 1 rollout x 2 decode forwards at a context of 32 (%.1f s)" % secs1}
+    return out
+
+
+def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream):
+    """One pilot sequence of a fresh pilot pass, teacher-forced through the oracle at 12 steps spread over the context:
+    max-abs logit error and the two token agreements (the oracle's sampler on the GPU's logits / on its own)."""
+    import numpy as np
+    import torch
+    from oracle import decoder, philox, sampler
+    m, P, Lp, T = wl.model, wl.n_prompts, wl.prompt_len, wl.new_tokens
+    steps = sorted(set([0, 1, T - 1] + np.linspace(2, T - 2, 9).astype(int).tolist()))
+    seq = wl.n_pilot * (P // 2) + 1
+    with torch.cuda.stream(stream):
+        last = torch.empty((P, m.vocab), dtype=torch.float32, device=toks.device)
+        handles = pc.pc_prefill_shared(ctx, toks, cu, last, stream)
+        rows = np.repeat(np.arange(P, dtype=np.int32), wl.n_pilot)
+        seq_uids = (np.asarray(uids, np.int64)[:, None] * 65536 + np.arange(wl.n_pilot)[None, :]).reshape(-1)
+        g = pc.generate(ctx, handles[rows], rows, last, seq_uids, T, wl.temperature, seed, -1, 0.0, stream,
+                        keep_logits_rows=np.array([seq]), keep_logits_steps=steps)
+        pc.pc_release(ctx, handles, 1)
+    torch.cuda.synchronize()
+    gen = g["tokens"][seq].cpu().numpy()
+    gl = {t: lg[0].cpu().numpy() for t, lg in zip(g["logits_steps"], g["logits"])}
+    w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w_dev.items()}
+    full = np.concatenate([prompts[rows[seq]], gen])
+    want = decoder.forward_full(m, w_cpu, full[:-1], rows=[Lp - 1 + t for t in steps])
+    worst = sq = 0.0
+    same = own = 0
+    for a, t in enumerate(steps):
+        diff = want[a] - gl[t]
+        worst = max(worst, float(np.abs(diff).max()))
+        sq += float((diff ** 2).mean())
+        u = philox.sampling_uniform(seed, int(seq_uids[seq]), t)
+        same += int(sampler.sample_token(gl[t], wl.temperature, u)[0] == gen[t])
+        own += int(sampler.sample_token(want[a], wl.temperature, u)[0] == gen[t])
+    return {"positions": len(steps), "max_abs_logit_error": round(worst, 5),
+            "rms_logit_error": round(float(np.sqrt(sq / len(steps))), 6),
+            "tokens_from_gpu_logits": same, "tokens_from_oracle_logits": own,
+            "note": "one pilot sequence of the timed workload, teacher-forced through the float64 oracle; agreement from "
+                    "the oracle's own logits is bounded by ~1 - 0.4 sqrt(V) rms for the near-uniform distributions of a "
+                    "random-init model"}
 
 
 def main():
@@ -94,6 +159,7 @@ def main():
     ap.add_argument("--workload", default="C2")
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of one sequence of the workload")
     ap.add_argument("--verbose", action="store_true", help="report each phase on stderr as it completes")
     ap.add_argument("--eos-bias", default="0",
                     help="logit bias on the EOS id of the workloads that stop on EOS: a number, or 'ragged' for "
@@ -145,8 +211,23 @@ def main():
     kv_tokens = n_prompts_alive * Lp + n_max * (T + 64) + 4096
     if not args.no_score:   # the scoring leg runs every pilot rollout (prompt + completion) through the forward
         kv_tokens = max(kv_tokens, P * wl.n_pilot * (Lp + T + 64) + 4096)
-    ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=int(kv_tokens * m.kv_bytes_per_token() * 1.1),
-                     max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=max(P * Lp, n_max))
+    # The pool is sized for every prompt being kept, but never beyond what the GPU has left next to the caller's
+    # weights, the library's own copies, the activation buffers and the logits; a pass whose sequences do not fit is
+    # cut into waves (rollout.generate).
+    want_pool = int(kv_tokens * m.kv_bytes_per_token() * 1.1)
+    free_b, _total_b = torch.cuda.mem_get_info()
+    rows_max = max(P * Lp, n_max)
+    qd_, kvd_ = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    lib_bytes = (m.body_params() + m.lm_head_params()) * 2
+    act_bytes = rows_max * (4 * m.d_model + 4 * (qd_ + 2 * kvd_) + 2 * max(m.d_model, qd_) + 4 * qd_ + 2 * m.d_ff) + (64 << 20)
+    logit_bytes = 3 * n_max * m.vocab * 4 + (1024 * m.vocab * 4 if not args.no_score else 0)
+    pool = min(want_pool, int(free_b - lib_bytes - act_bytes - logit_bytes - (8 << 30)))
+    if pool < want_pool:
+        say_early = "KV pool %.1f GB of the %.1f GB an all-kept step would take: passes may run in waves" % (
+            pool / 2 ** 30, want_pool / 2 ** 30)
+        sys.stderr.write("[bench] " + say_early + "\n")
+    ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=pool,
+                     max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=rows_max)
     if args.no_graph:
         pc.pc_set_option(ctx, pc.PC_OPT_USE_GRAPH, 0)
     cu = (np.arange(P + 1) * Lp).astype(np.int32)
@@ -233,6 +314,7 @@ def main():
                                (wl.name, P, Lp, wl.n_pilot, wl.n_commit, T, m.n_layers, m.d_model, m.n_q_heads,
                                 m.n_kv_heads, m.head_dim, m.d_ff, m.vocab),
                    "eos_logit_bias": round(eos_bias, 3),
+                   "kv_pool_GB": round(pool / 2 ** 30, 1),
                    "kept_prompts": [int(o["counts"][0]) for o in outs],
                    "rollouts": [int(o["rollouts"]) for o in outs]},
         "roofline": roof,
@@ -336,6 +418,9 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    if not args.no_parity and eos_id < 0 and m.dtype == "bf16":
+        result["parity"] = parity_sample(pc, ctx, wl, w, toks, cu, prompts, uids, wl.seed_sampler + 5, stream)
+    result["saturated_stores"] = pc.pc_saturation_count(ctx)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, w, prompts, uids, wl.seed_sampler)
     ctx.close()

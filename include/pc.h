@@ -134,6 +134,8 @@ pc_status pc_set_option(pc_ctx *ctx, int32_t option, int32_t value);
  * bracket itself costs).  SYNCHRONISES on the recorded events.  reset != 0 recycles them. */
 pc_status pc_timing_read(pc_ctx *ctx, double *total_ms, int64_t *launches, double *empty_ms,
                          int64_t *empty_pairs, int32_t reset);
+/* Number of free slots / all slots of the context (a slot holds one live prompt or sequence). */
+pc_status pc_slots(const pc_ctx *ctx, int64_t *free_slots, int64_t *total_slots);
 /* Number of activation / KV-cache values that were clamped to +-65504 on their way into IEEE half since
  * the last reset (PC_ACT_F16 contexts; always 0 otherwise).  A non-zero count means the model's activations
  * leave the half range and the logits are no longer trustworthy: use PC_ACT_BF16 for such a model.
@@ -164,6 +166,12 @@ pc_status pc_prefill_shared(pc_ctx *ctx, const int32_t *prompt_tokens, const int
  *   seq_out  host int32 [n]: sequence ids (slot indices). */
 pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens,
                   int32_t *seq_out, void *stream);
+
+/* KV blocks a pc_fork of each entry would take from the pool (host bookkeeping, nothing changes): lets a
+ * caller cut a pass whose sequences do not all fit into waves (Section 3.4 binding on one GPU: the commit and
+ * pilot sequences of a step share the pool).  blocks_out: host int64 [n]. */
+pc_status pc_fork_need(const pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens,
+                       int64_t *blocks_out);
 
 /* One decode step pi_theta(o_t | q, o_<t) (Section 3.1) for n sequences:
  * feeds one token per sequence, appends its K/V to the cache, returns the

@@ -76,9 +76,11 @@ def library() -> C.CDLL:
             "pc_destroy": [vp],
             "pc_set_option": [vp, i32, i32],
             "pc_kv_blocks": [vp, C.POINTER(i64), C.POINTER(i64)],
+            "pc_slots": [vp, C.POINTER(i64), C.POINTER(i64)],
             "pc_timing_read": [vp, C.POINTER(C.c_double), C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(i64), i32],
             "pc_prefill_shared": [vp, vp, vp, i32, vp, vp, vp],
             "pc_fork": [vp, vp, i32, i32, vp, vp],
+            "pc_fork_need": [vp, vp, i32, i32, vp],
             "pc_decode_step": [vp, vp, vp, i32, vp, vp],
             "pc_decode_step_static": [vp, vp, vp, i32, vp, vp],
             "pc_release": [vp, vp, i32, i32],
@@ -165,6 +167,7 @@ class Context:
                      *[C.cast(self._arrays[n], C.POINTER(C.c_void_p)) for n in
                        ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down")])
         cc = _CacheConfig(block_size, kv_pool_bytes, max_slots, max_ctx, max_batch_rows)
+        self.max_slots, self.max_batch_rows = int(max_slots), int(max_batch_rows)
         h = C.c_void_p()
         _check(lib.pc_create(C.byref(mc), C.byref(w), C.byref(cc), C.byref(h)))
         self._h = h
@@ -215,6 +218,12 @@ def pc_kv_blocks(ctx: Context):
     return f.value, t.value
 
 
+def pc_slots(ctx: Context):
+    f, t = C.c_int64(), C.c_int64()
+    _check(library().pc_slots(ctx.handle, C.byref(f), C.byref(t)))
+    return f.value, t.value
+
+
 def pc_prefill_shared(ctx: Context, prompt_tokens: torch.Tensor, cu_lens, last_logits: torch.Tensor, stream=None):
     """prompt_tokens: device int32 (packed); cu_lens: host int32 [P+1];
     last_logits: device fp32 [P, vocab] (written).  Returns handles (numpy int32 [P])."""
@@ -238,6 +247,14 @@ def pc_fork(ctx: Context, prompt_handle, max_new_tokens: int, stream=None) -> np
     out = np.zeros(max(len(ph), 1), np.int32)
     _check(library().pc_fork(ctx.handle, ph.ctypes.data, len(ph), int(max_new_tokens), out.ctypes.data,
                              _stream_ptr(stream)))
+    return out[:len(ph)]
+
+
+def pc_fork_need(ctx: Context, prompt_handle, max_new_tokens: int) -> np.ndarray:
+    """KV blocks a fork of each handle would take (int64 [n]); changes nothing."""
+    ph = _host_i32(prompt_handle, "prompt_handle")
+    out = np.zeros(max(len(ph), 1), np.int64)
+    _check(library().pc_fork_need(ctx.handle, ph.ctypes.data, len(ph), int(max_new_tokens), out.ctypes.data))
     return out[:len(ph)]
 
 

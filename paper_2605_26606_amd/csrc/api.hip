@@ -283,9 +283,13 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
     // projection rotates q and k and appends k and v itself; the output projection updates the residual stream and
     // leaves the new rows times the next RMSNorm's gain plus that norm's row statistics, and the gate/up epilogue
     // applies the norm's scale.
+    // (the fused projections own whole-K 64 x 32 tiles and re-read the activation rows once per 32 output columns:
+    // that pays up to a few million weights per projection -- the 1.5B shape -- and loses to the K-sliced kernels
+    // beyond, measured at the 8B shape)
     const bool fused = !row_pos && ctx->fuse_decode && impl == 1 && ctx->mfma_attention() && ctx->qkv_perm &&
                        skinny_ok(rows, qd + 2 * kvd, m.d_model, m.head_dim) &&
-                       skinny_ok(rows, m.d_model, qd, m.head_dim);
+                       skinny_ok(rows, m.d_model, qd, m.head_dim) &&
+                       (int64_t)(qd + 2 * kvd) * m.d_model <= ((int64_t)8 << 20);
     for (int l = 0; l < m.n_layers; ++l) {
         launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, pending,
                        sat, st);
@@ -843,6 +847,28 @@ pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, c
     ctx->dec_seq.clear();
     ctx->list_version++;
     return rc;
+}
+
+pc_status pc_slots(const pc_ctx *ctx, int64_t *free_slots, int64_t *total_slots) {
+    if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_slots: null context");
+    if (free_slots) *free_slots = (int64_t)ctx->free_slots.size();
+    if (total_slots) *total_slots = (int64_t)ctx->c.max_slots;
+    return PC_OK;
+}
+
+pc_status pc_fork_need(const pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens,
+                       int64_t *blocks_out) {
+    if (!ctx || n < 0 || max_new_tokens < 0 || (n > 0 && (!prompt_handle || !blocks_out)))
+        PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork_need: null argument or negative count");
+    const int bs = ctx->c.block_size;
+    for (int i = 0; i < n; ++i) {
+        const int h = prompt_handle[i];
+        if (h < 0 || h >= ctx->c.max_slots || !ctx->slots[h].used || !ctx->slots[h].is_prompt)
+            PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork_need: entry %d is not a live prompt handle", i);
+        const int len = ctx->slots[h].len;
+        blocks_out[i] = (len + max_new_tokens + bs - 1) / bs - len / bs;
+    }
+    return PC_OK;
 }
 
 pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t max_new_tokens, int32_t *seq_out,

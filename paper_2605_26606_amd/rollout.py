@@ -22,7 +22,63 @@ def _seq_uids(prompt_uids: np.ndarray, rollout_indices) -> np.ndarray:
     return (np.asarray(prompt_uids, dtype=np.int64)[:, None] * 65536 + r[None, :]).reshape(-1)
 
 
+def plan_waves(ctx: B.Context, handles: np.ndarray, new_tokens: int, free_slots_reserve: int = 0):
+    """Cuts the sequences (one per entry of `handles`, rollouts of a prompt next to each other) into consecutive
+    waves that each fit the free KV blocks, the free slots and the activation buffers of the context; a prompt's
+    rollouts stay in one wave.  -> list of (begin, end).  Raises if a single prompt's group does not fit."""
+    n = len(handles)
+    if n == 0:
+        return []
+    need = B.pc_fork_need(ctx, handles, new_tokens)
+    free_blocks, _ = B.pc_kv_blocks(ctx)
+    max_rows = min(ctx.max_batch_rows, B.pc_slots(ctx)[0] - free_slots_reserve)   # a sequence takes a slot
+    bounds = [0]
+    for i in range(1, n + 1):
+        if i == n or handles[i] != handles[i - 1]:
+            bounds.append(i)
+    waves, b, blocks, rows = [], 0, 0, 0
+    for g0, g1 in zip(bounds[:-1], bounds[1:]):
+        gb, gr = int(need[g0:g1].sum()), g1 - g0
+        if gb > free_blocks or gr > max_rows:
+            raise B.PcError(-2, "one prompt's %d rollouts need %d KV blocks / %d rows; the pool has %d free, a decode "
+                                "step holds %d rows" % (gr, gb, gr, free_blocks, max_rows))
+        if blocks + gb > free_blocks or rows + gr > max_rows:
+            waves.append((b, g0))
+            b, blocks, rows = g0, 0, 0
+        blocks += gb
+        rows += gr
+    waves.append((b, n))
+    return waves
+
+
 def generate(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_logits: torch.Tensor,
+             seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
+             eos_logit_bias: float = 0.0, stream=None, **kw):
+    """generate_wave over as many waves as the KV pool makes necessary (Section 3.4: on one GPU the pool is shared
+    by everything that decodes): when the sequences' reserved blocks do not all fit, the pass is cut into
+    consecutive waves, each decoded to the end and released before the next is forked.  A sequence's tokens depend
+    on its uid and step only, never on the wave it ran in.  Same arguments and result as generate_wave; logits can
+    only be kept (keep_logits_rows) when the pass fits one wave."""
+    handles = np.ascontiguousarray(handles, dtype=np.int32)
+    waves = plan_waves(ctx, handles, int(new_tokens))
+    if len(waves) <= 1:
+        return generate_wave(ctx, handles, logit_rows, first_logits, seq_uids, new_tokens, temperature, seed, eos_id,
+                             eos_logit_bias, stream, **kw)
+    if kw.get("keep_logits_rows") is not None:
+        raise ValueError("logits can only be kept when the pass fits one wave (%d needed)" % len(waves))
+    outs = []
+    for b, e in waves:
+        outs.append(generate_wave(ctx, handles[b:e], np.asarray(logit_rows)[b:e], first_logits, np.asarray(seq_uids)[b:e],
+                                  new_tokens, temperature, seed, eos_id, eos_logit_bias, stream, **kw))
+    out = dict(tokens=torch.cat([o["tokens"] for o in outs]), lengths=torch.cat([o["lengths"] for o in outs]),
+               steps_run=sum(o["steps_run"] for o in outs), rows_decoded=sum(o["rows_decoded"] for o in outs),
+               logits=[], logits_rows=[], logits_steps=[], waves=len(waves))
+    if "logprobs" in outs[0]:
+        out["logprobs"] = torch.cat([o["logprobs"] for o in outs])
+    return out
+
+
+def generate_wave(ctx: B.Context, handles: np.ndarray, logit_rows: np.ndarray, first_logits: torch.Tensor,
              seq_uids: np.ndarray, new_tokens: int, temperature: float, seed: int, eos_id: int = -1,
              eos_logit_bias: float = 0.0, stream=None, keep_logits_rows: Optional[np.ndarray] = None,
              poll_every: int = 64, time_class: int = -1, time_every: int = 0, timed_steps: Optional[list] = None,

@@ -347,3 +347,48 @@ def test_step_with_top_p_and_variance_filter_matches_oracle():
     assert np.abs(got["advantages"].reshape(-1) - adv).max() <= 5e-7
     if same and np.array_equal(got["commit_idx"], want["commit_idx"]):
         assert np.array_equal(got["commit_tokens"], want["commit_tokens"])
+
+
+def test_small_pool_forces_waves_and_tokens_do_not_change():
+    # KV-pool wave scheduling: a pool that holds the prompts and about a third of the pass's sequences cuts both
+    # passes into waves; on the fp32 model (row-independent kernels) every token, reward, class and advantage equals
+    # the one-wave result exactly, and the pool is empty afterwards
+    import paper_2605_26606_amd as pc
+    wl = workloads.scaled(workloads.WORKLOADS["C1"], n_prompts=10, new_tokens=40)
+    say("wave scheduling on a small KV pool")
+    w = workloads.make_weights(wl.model, wl.seed_weights)
+    prompts = workloads.make_prompts(wl.n_prompts, wl.prompt_len, wl.model.vocab, wl.seed_prompts)
+    uids = workloads.make_prompt_uids(wl.n_prompts)
+    kw = dict(block_size=32, max_slots=256, max_ctx=96, max_batch_rows=512)
+    big = _step(wl, w, prompts, uids, wl.seed_sampler, kv_pool_bytes=64 << 20, **kw)
+    # one block of 32 tokens over 2 layers x 2 kv heads x (K + V) x 32 dims x 4 bytes = 32 KiB; prompts take 10
+    # blocks, a sequence reserves 2 (32 + 40 tokens -> 3 blocks, the first shared): 40 pilot sequences would need 80
+    block_bytes = 2 * 2 * 2 * 32 * 32 * 4
+    ctx = make_ctx(wl.model, w, kv_pool_bytes=block_bytes * (10 + 30), **kw)
+    P, Lp = prompts.shape
+    cu = (np.arange(P + 1) * Lp).astype(np.int32)
+    toks = torch.from_numpy(prompts.reshape(-1).astype(np.int32)).cuda()
+    with torch.cuda.stream(side_stream()):
+        last = torch.empty((P, wl.model.vocab), dtype=torch.float32, device="cuda")
+        handles = pc.pc_prefill_shared(ctx, toks, cu, last)
+        rows = np.repeat(np.arange(P, dtype=np.int32), wl.n_pilot)
+        waves = pc.plan_waves(ctx, handles[rows], wl.new_tokens)
+        assert len(waves) == 4 and waves[0][0] == 0 and waves[-1][1] == 40       # 3 + 3 + 3 + 1 prompts
+        assert all((e - b) % wl.n_pilot == 0 for b, e in waves)          # a prompt's rollouts stay together
+        pc.pc_release(ctx, handles, 1)
+        small = pc.pilot_commit_step(ctx, wl, toks, cu, uids, wl.seed_sampler)
+    torch.cuda.synchronize()
+    assert pc.pc_kv_blocks(ctx)[0] == pc.pc_kv_blocks(ctx)[1] and pc.pc_slots(ctx)[0] == pc.pc_slots(ctx)[1]
+    ctx.close()
+    for k in ("pilot_tokens", "pilot_rewards", "p_hat", "cls", "evict", "commit_idx", "commit_tokens", "commit_rewards",
+              "union_rewards", "advantages", "counts"):
+        a = small[k].cpu().numpy() if isinstance(small[k], torch.Tensor) else small[k]
+        assert np.array_equal(a, big[k]), k
+    assert small["rollouts"] == big["rollouts"] and small["tokens_generated"] == big["tokens_generated"]
+    # a pool too small for a single prompt's group is an error, not a hang
+    ctx = make_ctx(wl.model, w, kv_pool_bytes=block_bytes * (10 + 5), **kw)
+    with torch.cuda.stream(side_stream()):
+        with pytest.raises(pc.PcError) as e:
+            pc.pilot_commit_step(ctx, wl, toks, cu, uids, wl.seed_sampler)
+    assert e.value.code == -2
+    ctx.close()
