@@ -9,6 +9,7 @@
 #include <new>
 #include <vector>
 
+#include "kv_book.h"
 #include "pc_internal.h"
 
 // Scratch of pc_decode_step_static, the decode step that allocates nothing: one fixed array per GPU in the
@@ -28,16 +29,6 @@ void set_error(const char *fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
 }
-
-struct Slot {
-    bool used = false;
-    bool is_prompt = false;
-    int len = 0;          // tokens whose K/V are in the cache
-    int capacity = 0;     // tokens the slot's blocks can hold
-    int limit = 0;        // tokens the slot may hold: prompt length + reserved new tokens, at most max_ctx
-    int prompt = -1;      // sequences: the prompt slot they were forked from
-    std::vector<int32_t> blocks;
-};
 
 // Pinned host staging for the small control arrays that go to the device (block-table rows, row
 // metadata, sequence lists).  An asynchronous copy reads its host source when the stream reaches it, so
@@ -122,9 +113,7 @@ struct pc_ctx {
     int64_t n_blocks = 0;
     int max_blocks_per_slot = 0;
     int32_t *d_block_table = nullptr, *d_slot_len = nullptr;
-    std::vector<int32_t> h_table, h_len;
-    std::vector<int32_t> refcnt, free_blocks, free_slots;
-    std::vector<Slot> slots;
+    KvBook book;   // slots, block lists, reference counts, free lists, host mirrors of the device tables
     float *rope_cos = nullptr, *rope_sin = nullptr;
     // activations
     float *h = nullptr, *qkv = nullptr, *attn_scratch = nullptr;
@@ -219,27 +208,14 @@ pc_status upload_slots(pc_ctx *ctx, int s0, int s1, hipStream_t st) {
     const int per = std::max<int>(1, (int)(ctx->stage.cap / 4 / (w * sizeof(int32_t))));
     for (int a = s0; a <= s1; a += per) {
         const int b = std::min(s1, a + per - 1);
-        pc_status rc = ctx->stage.push(ctx->d_block_table + (size_t)a * w, ctx->h_table.data() + (size_t)a * w,
+        pc_status rc = ctx->stage.push(ctx->d_block_table + (size_t)a * w, ctx->book.h_table.data() + (size_t)a * w,
                                        (size_t)(b - a + 1) * w * sizeof(int32_t), st);
         if (rc != PC_OK) return rc;
     }
-    return ctx->stage.push(ctx->d_slot_len + s0, ctx->h_len.data() + s0, (size_t)(s1 - s0 + 1) * sizeof(int32_t), st);
+    return ctx->stage.push(ctx->d_slot_len + s0, ctx->book.h_len.data() + s0, (size_t)(s1 - s0 + 1) * sizeof(int32_t), st);
 }
 
-void write_table_row(pc_ctx *ctx, int slot) {
-    const Slot &s = ctx->slots[slot];
-    int32_t *row = ctx->h_table.data() + (size_t)slot * ctx->max_blocks_per_slot;
-    for (size_t i = 0; i < s.blocks.size(); ++i) row[i] = s.blocks[i];
-    ctx->h_len[slot] = s.len;
-}
-
-void release_slot(pc_ctx *ctx, int slot) {
-    Slot &s = ctx->slots[slot];
-    for (int32_t b : s.blocks)
-        if (--ctx->refcnt[b] == 0) ctx->free_blocks.push_back(b);
-    s = Slot();
-    ctx->free_slots.push_back(slot);
-}
+void release_slot(pc_ctx *ctx, int slot) { ctx->book.release(slot); }
 
 // Brackets a launch with an event pair when its class is being timed.
 struct Timed {
@@ -526,13 +502,7 @@ pc_status pc_create(const pc_model_config *model, const pc_weights *w, const pc_
     TRY(dev_alloc(&ctx->d_slot_len, (size_t)cache->max_slots));
     TRY_HIP(hipMemsetAsync(ctx->d_block_table, 0, (size_t)cache->max_slots * ctx->max_blocks_per_slot * 4, st));
     TRY_HIP(hipMemsetAsync(ctx->d_slot_len, 0, (size_t)cache->max_slots * 4, st));
-    ctx->h_table.assign((size_t)cache->max_slots * ctx->max_blocks_per_slot, 0);
-    ctx->h_len.assign(cache->max_slots, 0);
-    ctx->refcnt.assign((size_t)ctx->n_blocks, 0);
-    ctx->free_blocks.reserve((size_t)ctx->n_blocks);
-    for (int64_t b = ctx->n_blocks - 1; b >= 0; --b) ctx->free_blocks.push_back((int32_t)b);
-    ctx->slots.resize(cache->max_slots);
-    for (int s = cache->max_slots - 1; s >= 0; --s) ctx->free_slots.push_back(s);
+    ctx->book.init(bs, cache->max_slots, cache->max_ctx, ctx->n_blocks);
     ctx->stamp.assign(cache->max_slots, 0);
 
     // ---- rotary tables, angles in double
@@ -652,7 +622,7 @@ pc_status pc_saturation_count(pc_ctx *ctx, int64_t *count, int32_t reset) {
 
 pc_status pc_kv_blocks(const pc_ctx *ctx, int64_t *free_blocks, int64_t *total_blocks) {
     if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_kv_blocks: null context");
-    if (free_blocks) *free_blocks = (int64_t)ctx->free_blocks.size();
+    if (free_blocks) *free_blocks = (int64_t)ctx->book.free_blocks.size();
     if (total_blocks) *total_blocks = ctx->n_blocks;
     return PC_OK;
 }
@@ -686,30 +656,15 @@ static pc_status forward_sequences(pc_ctx *ctx, const int32_t *prompt_tokens, co
             PC_FAIL(PC_ERR_INVALID_ARG, "forward: prompt %d longer than max_batch_rows", p);
         need_blocks += (len + bs - 1) / bs;
     }
-    if ((size_t)P > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "forward: out of slots");
-    if ((size_t)need_blocks > ctx->free_blocks.size())
+    if ((size_t)P > ctx->book.free_slots.size()) PC_FAIL(PC_ERR_OOM, "forward: out of slots");
+    if ((size_t)need_blocks > ctx->book.free_blocks.size())
         PC_FAIL(PC_ERR_OOM, "forward: needs %lld KV blocks, %zu free", (long long)need_blocks,
-                ctx->free_blocks.size());
+                ctx->book.free_blocks.size());
     // ---- allocate
     int smin = ctx->c.max_slots, smax = -1;
     for (int p = 0; p < P; ++p) {
         const int len = cu_lens[p + 1] - cu_lens[p];
-        const int slot = ctx->free_slots.back();
-        ctx->free_slots.pop_back();
-        Slot &s = ctx->slots[slot];
-        s.used = true;
-        s.is_prompt = true;
-        s.len = len;
-        const int nb = (len + bs - 1) / bs;
-        s.capacity = nb * bs;
-        s.limit = len;
-        for (int i = 0; i < nb; ++i) {
-            const int32_t b = ctx->free_blocks.back();
-            ctx->free_blocks.pop_back();
-            ctx->refcnt[b] = 1;
-            s.blocks.push_back(b);
-        }
-        write_table_row(ctx, slot);
+        const int slot = ctx->book.take_prompt(len);
         handle_out[p] = slot;
         smin = std::min(smin, slot);
         smax = std::max(smax, slot);
@@ -843,7 +798,7 @@ pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, c
     // the sequences were only passing through: their slots and blocks go back (work already enqueued keeps its
     // place in the stream ahead of whoever reuses them)
     for (int32_t h : handles)
-        if (h >= 0 && ctx->slots[h].used) release_slot(ctx, h);
+        if (h >= 0 && ctx->book.slots[h].used) release_slot(ctx, h);
     ctx->dec_seq.clear();
     ctx->list_version++;
     return rc;
@@ -851,7 +806,7 @@ pc_status pc_score(pc_ctx *ctx, const int32_t *tokens, const int32_t *cu_lens, c
 
 pc_status pc_slots(const pc_ctx *ctx, int64_t *free_slots, int64_t *total_slots) {
     if (!ctx) PC_FAIL(PC_ERR_INVALID_ARG, "pc_slots: null context");
-    if (free_slots) *free_slots = (int64_t)ctx->free_slots.size();
+    if (free_slots) *free_slots = (int64_t)ctx->book.free_slots.size();
     if (total_slots) *total_slots = (int64_t)ctx->c.max_slots;
     return PC_OK;
 }
@@ -863,9 +818,9 @@ pc_status pc_fork_need(const pc_ctx *ctx, const int32_t *prompt_handle, int32_t 
     const int bs = ctx->c.block_size;
     for (int i = 0; i < n; ++i) {
         const int h = prompt_handle[i];
-        if (h < 0 || h >= ctx->c.max_slots || !ctx->slots[h].used || !ctx->slots[h].is_prompt)
+        if (h < 0 || h >= ctx->c.max_slots || !ctx->book.slots[h].used || !ctx->book.slots[h].is_prompt)
             PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork_need: entry %d is not a live prompt handle", i);
-        const int len = ctx->slots[h].len;
+        const int len = ctx->book.slots[h].len;
         blocks_out[i] = (len + max_new_tokens + bs - 1) / bs - len / bs;
     }
     return PC_OK;
@@ -881,47 +836,22 @@ pc_status pc_fork(pc_ctx *ctx, const int32_t *prompt_handle, int32_t n, int32_t 
     int64_t need_blocks = 0;
     for (int i = 0; i < n; ++i) {
         const int h = prompt_handle[i];
-        if (h < 0 || h >= ctx->c.max_slots || !ctx->slots[h].used || !ctx->slots[h].is_prompt)
+        if (h < 0 || h >= ctx->c.max_slots || !ctx->book.slots[h].used || !ctx->book.slots[h].is_prompt)
             PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: entry %d is not a live prompt handle", i);
-        const int len = ctx->slots[h].len;
+        const int len = ctx->book.slots[h].len;
         if (len + max_new_tokens > ctx->c.max_ctx)
             PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: prompt length %d + %d new tokens exceeds max_ctx %d", len,
                     max_new_tokens, ctx->c.max_ctx);
         need_blocks += (len + max_new_tokens + bs - 1) / bs - len / bs;
     }
-    if ((size_t)n > ctx->free_slots.size()) PC_FAIL(PC_ERR_OOM, "pc_fork: out of slots");
-    if ((size_t)need_blocks > ctx->free_blocks.size())
-        PC_FAIL(PC_ERR_OOM, "pc_fork: needs %lld KV blocks, %zu free", (long long)need_blocks, ctx->free_blocks.size());
+    if ((size_t)n > ctx->book.free_slots.size()) PC_FAIL(PC_ERR_OOM, "pc_fork: out of slots");
+    if ((size_t)need_blocks > ctx->book.free_blocks.size())
+        PC_FAIL(PC_ERR_OOM, "pc_fork: needs %lld KV blocks, %zu free", (long long)need_blocks, ctx->book.free_blocks.size());
     if ((size_t)n > (size_t)ctx->c.max_slots) PC_FAIL(PC_ERR_INVALID_ARG, "pc_fork: too many sequences");
     std::vector<int32_t> pairs;
     int smin = ctx->c.max_slots, smax = -1;
     for (int i = 0; i < n; ++i) {
-        const Slot &ps = ctx->slots[prompt_handle[i]];
-        const int slot = ctx->free_slots.back();
-        ctx->free_slots.pop_back();
-        Slot &s = ctx->slots[slot];
-        s.used = true;
-        s.is_prompt = false;
-        s.prompt = prompt_handle[i];
-        s.len = ps.len;
-        const int n_full = ps.len / bs, total = (ps.len + max_new_tokens + bs - 1) / bs;
-        for (int b = 0; b < n_full; ++b) {
-            s.blocks.push_back(ps.blocks[b]);
-            ctx->refcnt[ps.blocks[b]]++;
-        }
-        for (int b = n_full; b < total; ++b) {
-            const int32_t nb = ctx->free_blocks.back();
-            ctx->free_blocks.pop_back();
-            ctx->refcnt[nb] = 1;
-            s.blocks.push_back(nb);
-            if (b == n_full && ps.len % bs) {   // partially filled prompt block: private copy
-                pairs.push_back(ps.blocks[b]);
-                pairs.push_back(nb);
-            }
-        }
-        s.capacity = total * bs;
-        s.limit = ps.len + max_new_tokens;
-        write_table_row(ctx, slot);
+        const int slot = ctx->book.take_fork(prompt_handle[i], max_new_tokens, pairs);
         seq_out[i] = slot;
         smin = std::min(smin, slot);
         smax = std::max(smax, slot);
@@ -950,7 +880,7 @@ pc_status pc_release(pc_ctx *ctx, const int32_t *ids, int32_t n, int32_t kind) {
     if (kind != 0 && kind != 1) PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: kind must be 0 (sequence) or 1 (prompt)");
     for (int i = 0; i < n; ++i) {
         const int s = ids[i];
-        if (s < 0 || s >= ctx->c.max_slots || !ctx->slots[s].used || ctx->slots[s].is_prompt != (kind == 1))
+        if (s < 0 || s >= ctx->c.max_slots || !ctx->book.slots[s].used || ctx->book.slots[s].is_prompt != (kind == 1))
             PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: entry %d is not a live %s", i, kind ? "prompt" : "sequence");
         for (int j = 0; j < i; ++j)
             if (ids[j] == s) PC_FAIL(PC_ERR_INVALID_ARG, "pc_release: entry %d repeats", i);
@@ -969,24 +899,24 @@ static pc_status prepare_decode(pc_ctx *ctx, const int32_t *seq, const int32_t *
     const int32_t gen = ++ctx->stamp_gen;
     for (int i = 0; i < n; ++i) {
         const int s = seq[i];
-        if (s < 0 || s >= ctx->c.max_slots || !ctx->slots[s].used || ctx->slots[s].is_prompt)
+        if (s < 0 || s >= ctx->c.max_slots || !ctx->book.slots[s].used || ctx->book.slots[s].is_prompt)
             PC_FAIL(PC_ERR_INVALID_ARG, "%s: entry %d is not a live sequence", who, i);
         if (ctx->stamp[s] == gen) PC_FAIL(PC_ERR_INVALID_ARG, "%s: sequence %d repeats", who, s);
         ctx->stamp[s] = gen;
-        if (ctx->slots[s].len >= ctx->slots[s].limit)
+        if (ctx->book.slots[s].len >= ctx->book.slots[s].limit)
             PC_FAIL(PC_ERR_INVALID_ARG, "%s: sequence %d already holds its %d tokens (prompt + reserved new tokens)", who,
-                    s, ctx->slots[s].limit);
+                    s, ctx->book.slots[s].limit);
     }
     if ((int)ctx->dec_seq.size() != n || memcmp(ctx->dec_seq.data(), seq, (size_t)n * 4) != 0) {
         ctx->dec_seq.assign(seq, seq + n);   // within the capacity reserved at creation
         ctx->list_version++;
         // rollouts of one prompt that sit next to each other in the list share their prefix blocks
         int g = 1;
-        while (g < n && ctx->slots[seq[g]].prompt == ctx->slots[seq[0]].prompt) ++g;
+        while (g < n && ctx->book.slots[seq[g]].prompt == ctx->book.slots[seq[0]].prompt) ++g;
         bool uniform = (n % g == 0);
         for (int i = 0; uniform && i < n; i += g)
             for (int k = 1; k < g; ++k)
-                if (ctx->slots[seq[i + k]].prompt != ctx->slots[seq[i]].prompt) uniform = false;
+                if (ctx->book.slots[seq[i + k]].prompt != ctx->book.slots[seq[i]].prompt) uniform = false;
         ctx->dec_group = uniform ? g : 1;
         pc_status rc = ctx->stage.push(ctx->d_dec_slot, ctx->dec_seq.data(), (size_t)n * 4, st);
         if (rc == PC_OK) rc = ctx->stage.mark(st);
@@ -999,10 +929,7 @@ static pc_status prepare_decode(pc_ctx *ctx, const int32_t *seq, const int32_t *
 }
 
 static void advance_host_lengths(pc_ctx *ctx, const int32_t *seq, int32_t n) {
-    for (int i = 0; i < n; ++i) {
-        ctx->slots[seq[i]].len++;
-        ctx->h_len[seq[i]]++;
-    }
+    for (int i = 0; i < n; ++i) ctx->book.advance(seq[i]);
 }
 
 pc_status pc_decode_step(pc_ctx *ctx, const int32_t *seq, const int32_t *tokens_in, int32_t n, float *logits,
