@@ -10,10 +10,10 @@
 //   S^T[token][column] = K[token][:] . Q[column][:]      (two 16x16x32 products per 32 of head_dim)
 //   O[column][:]      += P[column][token] V[token][:]    (eight 16x16x32 products)
 // where a "column" is a query row: a head (decode) or a position (prefill).
-// K is stored [token][head_dim] and V transposed [head_dim][token] inside each
-// block, so both products read 16 contiguous bytes per lane straight from
-// global memory; no LDS staging is needed because every K/V byte is used by
-// exactly one wave.
+// Inside each block K and V are stored in the order of the products' operand
+// fragments (KvGeom), so both products read 16 contiguous bytes per lane and one
+// contiguous kilobyte per wave straight from global memory; no LDS staging is
+// needed because every K/V byte is used by exactly one wave.
 #include <algorithm>
 
 #include "pc_internal.h"
@@ -61,9 +61,9 @@ __global__ __launch_bounds__(64) void attention_simt_kernel(const T *__restrict_
         const int key = c0 + lane;
         float s = -INFINITY;
         if (key < ctx) {
-            const T *kp = base + (int64_t)table[key / bs] * kv.block_elems() + (int64_t)(key % bs) * hd;
+            const T *kp = base + (int64_t)table[key / bs] * kv.block_elems();
             float d = 0.f;
-            for (int i = 0; i < hd; ++i) d = fmaf(qs[i], to_f32(kp[i]), d);
+            for (int i = 0; i < hd; ++i) d = fmaf(qs[i], to_f32(kp[kv.k_index(key % bs, i)]), d);
             s = d;
         }
         const float m_new = fmaxf(m, wave_max_f(s));
@@ -78,12 +78,12 @@ __global__ __launch_bounds__(64) void attention_simt_kernel(const T *__restrict_
         const int nk = min(WAVE, ctx - c0);
         for (int j = 0; j < nk; ++j) {
             const int kj = c0 + j;
-            const T *vp = base + (int64_t)table[kj / bs] * kv.block_elems() + (int64_t)bs * hd + (kj % bs);
+            const T *vp = base + (int64_t)table[kj / bs] * kv.block_elems();
             const float pj = ps[j];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 int c = lane + WAVE * i;
-                if (c < hd) acc[i] = fmaf(pj, to_f32(vp[(int64_t)c * bs]), acc[i]);
+                if (c < hd) acc[i] = fmaf(pj, to_f32(vp[kv.v_index(kj % bs, c)]), acc[i]);
             }
         }
         __syncthreads();
@@ -141,21 +141,21 @@ template <typename T> struct KvTile {
     typename Mma<T>::frag ka[2][4], vf[8];
 };
 
-// The K and V fragments of the 32-token tile that starts at token t0 (lane layout as the products need it).
+// The K and V fragments of the 32-token tile that starts at token t0 (a multiple of 32).  The cache stores them
+// fragment-major (KvGeom): every fragment is one contiguous kilobyte, lane l reads its 16 bytes at offset 16 l.
 template <typename T>
 __device__ inline void load_kv_tile(const T *__restrict__ head_base, int64_t block_elems,
                                     const int32_t *__restrict__ table, int bs, int t0, KvTile<T> &kt) {
-    const int lane = threadIdx.x % WAVE, i = lane % 16, g = lane / 16;
-    const int krow = 8 * (i / 4) + (i % 4);   // tile u reads token krow + 4u: lane (column, g) then owns tokens 8g..8g+7
-    const int tin = t0 % bs;
-    const T *kb = head_base + (int64_t)table[t0 / bs] * block_elems;
+    const int lane = threadIdx.x % WAVE;
+    const int tile = (t0 % bs) >> 5;
+    const T *kb = head_base + (int64_t)table[t0 / bs] * block_elems + lane * 8;
     const T *vb = kb + (int64_t)bs * HD;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) kt.ka[u][kk] = ld_frag(kb + (int64_t)(tin + krow + 4 * u) * HD + 32 * kk + 8 * g);
+        for (int kk = 0; kk < 4; ++kk) kt.ka[u][kk] = ld_frag(kb + (((tile * 2 + u) * 4 + kk) << 9));
 #pragma unroll
-    for (int nn = 0; nn < 8; ++nn) kt.vf[nn] = ld_frag(vb + (int64_t)(16 * nn + i) * bs + tin + 8 * g);
+    for (int nn = 0; nn < 8; ++nn) kt.vf[nn] = ld_frag(vb + ((tile * 8 + nn) << 9));
 }
 
 // One tile's update of the running softmax state of NH query-head groups that share the kv head.

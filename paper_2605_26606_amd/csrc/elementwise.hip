@@ -177,19 +177,19 @@ __global__ __launch_bounds__(256) void rope_append_kernel(const float *__restric
     const int blk = kv.block_table[(int64_t)slot * kv.max_blocks_per_slot + pos / bs];
     const int tin = pos % bs;
     T *pool = (T *)kv.pool + (int64_t)layer * kv.layer_stride + (int64_t)blk * kv.block_elems();
-    if (item < nq + nk) {   // k heads -> K [tok][hd]
+    if (item < nq + nk) {   // k heads
         const int i = item - nq, head = i / half, j = i % half;
         const int koff = hq * hd;
         const float x1 = val(koff + head * hd + qk_col(j)), x2 = val(koff + head * hd + qk_col(j + half));
         const float c = rope_cos[(int64_t)pos * half + j], sgn = rope_sin[(int64_t)pos * half + j];
-        T *kd = pool + (int64_t)head * kv.head_elems() + (int64_t)tin * hd;
-        kd[j] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
-        kd[j + half] = from_f32_sat<T>(x2 * c + x1 * sgn, sat);
-    } else {                // v heads -> V^T [hd][tok]
+        T *kd = pool + (int64_t)head * kv.head_elems();
+        kd[kv.k_index(tin, j)] = from_f32_sat<T>(x1 * c - x2 * sgn, sat);
+        kd[kv.k_index(tin, j + half)] = from_f32_sat<T>(x2 * c + x1 * sgn, sat);
+    } else {                // v heads
         const int i = item - nq - nk, head = i / hd, j = i % hd;
         const int voff = (hq + hkv) * hd;
-        T *vd = pool + (int64_t)head * kv.head_elems() + (int64_t)bs * hd;
-        vd[(int64_t)j * bs + tin] = from_f32_sat<T>(val(voff + head * hd + j), sat);
+        T *vd = pool + (int64_t)head * kv.head_elems();
+        vd[kv.v_index(tin, j)] = from_f32_sat<T>(val(voff + head * hd + j), sat);
     }
 }
 

@@ -208,18 +208,18 @@ __global__ __launch_bounds__(64 * SK_WAVES) void gemm_skinny_kernel(const T *__r
             const int bs = qa.kv.block_size;
             const int blk = qa.kv.block_table[(int64_t)slot * qa.kv.max_blocks_per_slot + pos / bs];
             T *kd = (T *)qa.kv.pool + (int64_t)qa.layer * qa.kv.layer_stride + (int64_t)blk * qa.kv.block_elems() +
-                    (int64_t)head * qa.kv.head_elems() + (int64_t)(pos % bs) * hd + dim;
+                    (int64_t)head * qa.kv.head_elems() + qa.kv.k_index(pos % bs, dim);   // 8 dims: 16 contiguous bytes
             *(sk_u32x4 *)kd = pk;
         }
-    } else {               // a v head: plain order, V^T [hd][block_size]
+    } else {               // a v head
         const int c0 = n0 - qd - kvd;
         const int head = c0 / hd, d0 = c0 % hd + 8 * cg;
         const int bs = qa.kv.block_size;
         const int blk = qa.kv.block_table[(int64_t)slot * qa.kv.max_blocks_per_slot + pos / bs];
         T *vd = (T *)qa.kv.pool + (int64_t)qa.layer * qa.kv.layer_stride + (int64_t)blk * qa.kv.block_elems() +
-                (int64_t)head * qa.kv.head_elems() + (int64_t)bs * hd + (pos % bs);
+                (int64_t)head * qa.kv.head_elems();
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vd[(int64_t)(d0 + e) * bs] = from_f32_sat<T>(v8[e], sat);
+        for (int e = 0; e < 8; ++e) vd[qa.kv.v_index(pos % bs, d0 + e)] = from_f32_sat<T>(v8[e], sat);
     }
 }
 

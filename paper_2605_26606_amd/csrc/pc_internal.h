@@ -114,11 +114,19 @@ void set_error(const char *fmt, ...);
     } while (0)
 
 // ---------------------------------------------------------------- KV cache geometry
-// Pool layout: [layer][block][kv_head][K | V^T] with
-//   K    [block_size][head_dim]   (a token's key is contiguous)
-//   V^T  [head_dim][block_size]   (a head-dim row's values over the block's
-//                                  tokens are contiguous: the layout the
-//                                  P.V matrix-core product consumes)
+// Pool layout: [layer][block][kv_head][K | V], block_size * head_dim elements each.
+//
+// Fragment-major (head_dim a multiple of 32; block_size always is): inside a block the keys and values are stored
+// in the order in which the matrix-core attention kernels consume them, so that every operand fragment (64 lanes
+// x 16 bytes) is ONE contiguous kilobyte -- a wave-wide load then touches 8 cache lines instead of 64 separate
+// 16-byte pieces, which is what bounds a kernel that reads fragments straight from global memory (the load unit
+// takes about one request per two clocks per CU, whatever its size).
+//   K  tiles of 32 tokens; a tile is 2 x (head_dim / 32) fragments [u][kk]: lane (i, g) of fragment (u, kk) holds
+//      dims 32 kk + 8 g .. + 7 of token 8 (i / 4) + i % 4 + 4 u of the tile (the token order that leaves every lane of
+//      the score tile with 8 consecutive tokens, the operand layout of the P.V product)
+//   V  tiles of 32 tokens; a tile is head_dim / 16 fragments [nn]: lane (i, g) holds tokens 8 g .. 8 g + 7 of dim
+//      16 nn + i
+// Plain (any other head_dim): K [block_size][head_dim], V^T [head_dim][block_size].
 struct KvGeom {
     void *pool;
     int64_t layer_stride;   // elements between layers
@@ -129,6 +137,19 @@ struct KvGeom {
     const int32_t *block_table;   // device [max_slots][max_blocks_per_slot]
     __host__ __device__ int64_t block_elems() const { return (int64_t)n_kv_heads * 2 * block_size * head_dim; }
     __host__ __device__ int64_t head_elems() const { return (int64_t)2 * block_size * head_dim; }
+    __host__ __device__ bool frag_major() const { return (head_dim & 31) == 0; }
+    // element offsets of K[token tin][dim d] / V[token tin][dim d] inside one (block, kv head) region
+    __host__ __device__ int k_index(int tin, int d) const {
+        if (!frag_major()) return tin * head_dim + d;
+        const int tt = tin & 31, u = (tt >> 2) & 1, i = ((tt >> 3) << 2) | (tt & 3);
+        const int frag = ((tin >> 5) * 2 + u) * (head_dim >> 5) + (d >> 5);
+        return (frag << 9) + (((((d & 31) >> 3) << 4) + i) << 3) + (d & 7);
+    }
+    __host__ __device__ int v_index(int tin, int d) const {
+        if (!frag_major()) return block_size * head_dim + d * block_size + tin;
+        const int frag = (tin >> 5) * (head_dim >> 4) + (d >> 4);
+        return block_size * head_dim + (frag << 9) + (((((tin & 31) >> 3) << 4) + (d & 15)) << 3) + (tin & 7);
+    }
 };
 
 // Order of the weight rows (= output columns) of a q or k head for the fused decode projection: a 32-column
