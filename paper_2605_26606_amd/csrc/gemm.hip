@@ -102,9 +102,12 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 static constexpr int N_XCD = 8;   // MI355X: 8 accelerator dies, each with its own L2; workgroup i runs on die i % 8
 
 // One 32x32x16 product per instruction.  Operand layout (wave of 64 lanes):
-//   a: lane l holds A[row = l%32][k = 8*(l/32) .. +7]
-//   b: lane l holds B[k = 8*(l/32) .. +7][col = l%32]   (= W[n = l%32][k...], contiguous in memory)
+//   a: lane l holds X[row = l%32][k = 8*(l/32) .. +7]
+//   b: lane l holds Y[k = 8*(l/32) .. +7][col = l%32]
 //   d: lane l, element v holds D[row = 8*(v/4) + 4*(l/32) + v%4][col = l%32]
+// The kernel passes the WEIGHT fragment as a and the activation fragment as b (both are 8 consecutive k of one
+// matrix row, contiguous in memory), so d is the transposed output tile: lane l holds output row l%32 and, per
+// group of four elements, four consecutive output columns.
 //
 // Work decomposition: a 1-D grid; workgroup id -> (m block, n block, K slice) such that the m blocks
 // that share a weight tile run on the same die back to back (the second one finds the tile in L2).
@@ -274,7 +277,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int jj = 0; jj < TN; ++jj)
-                    acc[i][jj] = product(fa[kk & 1][i], fb[kk & 1][jj], acc[i][jj]);
+                    acc[i][jj] = product(fb[kk & 1][jj], fa[kk & 1][i], acc[i][jj]);   // weights as rows: the tile comes out transposed
             // instruction order asked of the compiler: after each matrix instruction one or two LDS fragment
             // reads and one global->LDS load, instead of all reads in a burst behind the last product
             // (measured: +5 % on the prefill shapes, neutral on the decode shapes)
@@ -293,24 +296,26 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     // (behind the first tile loads, so that the pipeline is already filling while the statistics arrive; these are
     // ordinary loads, younger than the tile loads: once they are back, so are the tiles)
     if constexpr (EPI == EPI_SWIGLU_RS) {
-        static_assert(64 * WM * WN >= 2 * BM || EPI != EPI_SWIGLU_RS, "two threads per row");
-        const int r = tid % BM, part = tid / BM;       // part 0: even rounds of tiles, part 1: odd rounds
-        if (part < 2) {
+        constexpr int PARTS = (64 * NW >= 2 * BM) ? 2 : 1;   // threads per row (each sums every PARTS-th round of tiles)
+        static_assert(64 * NW >= BM, "a thread per row");
+        const int r = tid % BM, part = tid / BM;
+        float ss = 0.f;
+        if (part < PARTS) {
             const int row = min(m0 + r, M - 1);
-            float ss = 0.f;
-            for (int t0 = part * RS_MAXT; t0 < rsc.tiles; t0 += 2 * RS_MAXT) {
+            for (int t0 = part * RS_MAXT; t0 < rsc.tiles; t0 += PARTS * RS_MAXT) {
                 float v[RS_MAXT];
 #pragma unroll
                 for (int u = 0; u < RS_MAXT; ++u) v[u] = (t0 + u < rsc.tiles) ? rsc.ssq[(int64_t)(t0 + u) * M + row] : 0.f;
 #pragma unroll
                 for (int u = 0; u < RS_MAXT; ++u) ss += v[u];
             }
+        }
+        if (PARTS == 2) {
             if (part == 1) s_rs_part[r] = ss;
             __syncthreads();
-            if (part == 0) s_rs[r] = 1.0f / sqrtf((ss + s_rs_part[r]) / (float)rsc.d + rsc.eps);
-        } else {
-            __syncthreads();
+            if (part == 0) ss += s_rs_part[r];
         }
+        if (part == 0) s_rs[r] = 1.0f / sqrtf(ss / (float)rsc.d + rsc.eps);
         __syncthreads();
     }
     int stage = 0;
@@ -329,85 +334,91 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     wait_vmcnt_le<0>();   // nothing may still be writing LDS when the block retires
 
     // ---- epilogue
-    if constexpr (M16) {   // lane (column lane%16, g = lane/16) holds rows 4g .. 4g+3 of each 16x16 tile
-        const int col_l = lane % 16, row_l = 4 * (lane / 16);
+    // The products take the weights as the row operand, so the accumulators hold the TRANSPOSED tile: a lane owns ONE
+    // output row m (m = lane % RT of the tile) and, per tile, runs of four consecutive output columns.  Written out
+    // from there, an output row would leave in 2- or 4-byte pieces, one store instruction per value -- hundreds of
+    // stores in flight per wave, which the store path takes far longer to retire than the bytes need (measured: a
+    // fifth of the decode gate/up kernel).  Instead each wave turns RT output rows at a time into whole rows through
+    // a private piece of the now idle LDS ring and stores them 16 bytes per lane, neighbouring lanes on
+    // neighbouring addresses.  LDS instructions of one wave execute in order, so the hand-over needs no barrier.
+    typedef typename std::conditional<(EPI == EPI_STORE_F32 || EPI == EPI_RESID_F32), float, T>::type OutT;
+    constexpr int WCOLS = SWIGLU ? (BN / WN) / 2 : BN / WN;        // output columns of one wave
+    constexpr int RB = WCOLS * (int)sizeof(OutT);                 // bytes of one output row of the wave
+    constexpr int LPR = RB / 16;                                  // lanes that store one row
+    constexpr int ROWS_PER = 64 / LPR;                            // rows one store instruction covers
+    constexpr int ITER = RT / ROWS_PER;
+    constexpr int PITCH = RB + 16;                                // bytes; the pad spreads the rows over the banks
+    constexpr int EPC = 16 / (int)sizeof(OutT);                   // output elements per 16-byte piece
+    static_assert(LPR >= 1 && LPR <= 64 && (64 % LPR) == 0 && ROWS_PER <= RT && ITER >= 1, "row pieces per wave");
+    static_assert((size_t)NW * RT * PITCH <= (size_t)NSTAGE * STAGE_ELEMS * sizeof(T), "staging fits the ring");
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();   // every wave has consumed its last fragments (they were waited for by the products)
+    asm volatile("" ::: "memory");
+    unsigned char *stg = smem_raw + (size_t)wave * RT * PITCH;
+    const int ml = lane % RT, nq = 4 * (lane / RT);               // the lane's row of a tile; first column of its runs
+    const int ldc = SWIGLU ? N / 2 : N;
+    const int colbase = SWIGLU ? (n0 + wn * (BN / WN)) / 2 : n0 + wn * (BN / WN);
+    OutT *Cbase = (OutT *)Cv + ((EPI == EPI_STORE_F32) ? (int64_t)z * M * N : 0);
+    auto put4 = [&](int col, float v0, float v1, float v2, float v3) {   // four consecutive columns of row ml
+        unsigned char *dst = stg + ml * PITCH + col * (int)sizeof(OutT);
+        if constexpr (sizeof(OutT) == 4) {
+            *(f32x4_t *)dst = (f32x4_t){v0, v1, v2, v3};
+        } else {
+            typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+            *(u32x2 *)dst = (u32x2){pack2_sat<T>(v0, v1, sat), pack2_sat<T>(v2, v3, sat)};
+        }
+    };
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rbase = m0 + wm * (BM / WM) + i * 16 + row_l;
-            if (SWIGLU) {
-                T *C = (T *)Cv;
+    for (int i = 0; i < TM; ++i) {
+        const float sc = (EPI == EPI_SWIGLU_RS) ? s_rs[wm * (BM / WM) + i * RT + ml] : 1.f;
+        if constexpr (SWIGLU) {
+            // a 64-wide chunk of weight rows = 32 gate rows, then the 32 matching up rows
+            if constexpr (M16) {
 #pragma unroll
-                for (int p2 = 0; p2 < TN / 4; ++p2)            // a 64-wide chunk = tiles 4p2, 4p2+1 (gate), 4p2+2, 4p2+3 (up)
+                for (int p2 = 0; p2 < TN / 4; ++p2)
 #pragma unroll
                     for (int q = 0; q < 2; ++q) {
-                        const int ncol = n0 + wn * (BN / WN) + 64 * p2;
-                        const int ocol = (ncol / 64) * 32 + 16 * q + col_l;
-                        if (ncol + 32 + 16 * q + col_l < N) {
-#pragma unroll
-                            for (int v = 0; v < 4; ++v) {
-                                const int row = rbase + v;
-                                const float sc = (EPI == EPI_SWIGLU_RS) ? s_rs[min(row - m0, BM - 1)] : 1.f;
-                                if (row < M)
-                                    C[(int64_t)row * (N / 2) + ocol] = from_f32_sat<T>(
-                                        silu_f(acc[i][4 * p2 + q][v] * sc) * (acc[i][4 * p2 + 2 + q][v] * sc), sat);
-                            }
-                        }
+                        const acc_t &ga = acc[i][4 * p2 + q], &ua = acc[i][4 * p2 + 2 + q];
+                        put4(32 * p2 + 16 * q + nq, silu_f(ga[0] * sc) * (ua[0] * sc), silu_f(ga[1] * sc) * (ua[1] * sc),
+                             silu_f(ga[2] * sc) * (ua[2] * sc), silu_f(ga[3] * sc) * (ua[3] * sc));
                     }
             } else {
 #pragma unroll
-                for (int jj = 0; jj < TN; ++jj) {
-                    const int col = n0 + wn * (BN / WN) + jj * 16 + col_l;
-                    if (col >= N) continue;
+                for (int p2 = 0; p2 < TN / 2; ++p2)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int row = rbase + v;
-                        if (row >= M) continue;
-                        if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
-                        if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
-                        if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32_sat<T>(acc[i][jj][v], sat);
+                    for (int vg = 0; vg < 4; ++vg) {
+                        const acc_t &ga = acc[i][2 * p2], &ua = acc[i][2 * p2 + 1];
+                        put4(32 * p2 + 8 * vg + nq, silu_f(ga[4 * vg] * sc) * (ua[4 * vg] * sc),
+                             silu_f(ga[4 * vg + 1] * sc) * (ua[4 * vg + 1] * sc),
+                             silu_f(ga[4 * vg + 2] * sc) * (ua[4 * vg + 2] * sc),
+                             silu_f(ga[4 * vg + 3] * sc) * (ua[4 * vg + 3] * sc));
                     }
-                }
-            }
-        }
-        return;
-    }
-    const int col_l = lane % 32;
-    const int row_l = 4 * (lane / 32);
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int rbase = m0 + wm * (BM / WM) + i * 32 + row_l;
-        if (SWIGLU) {
-            T *C = (T *)Cv;
-#pragma unroll
-            for (int p2 = 0; p2 < TN / 2; ++p2) {              // the wave's 64-wide chunks: 32 gate, 32 up columns
-                const int ncol = n0 + wn * (BN / WN) + 64 * p2;
-                const int ocol = (ncol / 64) * 32 + col_l;
-                if (ncol + 32 + col_l < N) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        int row = rbase + 8 * (v / 4) + (v % 4);
-                        const float sc = (EPI == EPI_SWIGLU_RS) ? s_rs[min(row - m0, BM - 1)] : 1.f;
-                        if (row < M)
-                            C[(int64_t)row * (N / 2) + ocol] =
-                                from_f32_sat<T>(silu_f(acc[i][2 * p2][v] * sc) * (acc[i][2 * p2 + 1][v] * sc), sat);
-                    }
-                }
             }
         } else {
 #pragma unroll
-            for (int jj = 0; jj < TN; ++jj) {
-                const int col = n0 + wn * (BN / WN) + jj * 32 + col_l;
-                if (col >= N) continue;
+            for (int jj = 0; jj < TN; ++jj)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int row = rbase + 8 * (v / 4) + (v % 4);
-                    if (row >= M) continue;
-                    if (EPI == EPI_STORE_F32) ((float *)Cv)[((int64_t)z * M + row) * N + col] = acc[i][jj][v];
-                    if (EPI == EPI_RESID_F32) ((float *)Cv)[(int64_t)row * N + col] += acc[i][jj][v];
-                    if (EPI == EPI_STORE_T) ((T *)Cv)[(int64_t)row * N + col] = from_f32_sat<T>(acc[i][jj][v], sat);
+                for (int vg = 0; vg < AV / 4; ++vg)
+                    put4(jj * RT + (M16 ? 0 : 8 * vg) + nq, acc[i][jj][4 * vg], acc[i][jj][4 * vg + 1],
+                         acc[i][jj][4 * vg + 2], acc[i][jj][4 * vg + 3]);
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int it = 0; it < ITER; ++it) {
+            const int row = it * ROWS_PER + lane / LPR, piece = lane % LPR;
+            const u32x4 val = *(const u32x4 *)(stg + row * PITCH + piece * 16);
+            const int gm = m0 + wm * (BM / WM) + i * RT + row, col = colbase + piece * EPC;
+            if (gm < M && col < ldc) {
+                OutT *dst = Cbase + (int64_t)gm * ldc + col;
+                if constexpr (EPI == EPI_RESID_F32) {
+                    const f32x4_t old = *(const f32x4_t *)dst, add = __builtin_bit_cast(f32x4_t, val);
+                    *(f32x4_t *)dst = (f32x4_t){old[0] + add[0], old[1] + add[1], old[2] + add[2], old[3] + add[3]};
+                } else {
+                    *(u32x4 *)dst = val;
                 }
             }
         }
+        __builtin_amdgcn_wave_barrier();
     }
 }
 
@@ -491,7 +502,8 @@ int launch_gemm(int dtype, int impl, const void *A, const void *W, void *C, int 
         gemm_simt<float>(A, W, C, M, N, K, epi, sat, s);
         return 1;
     }
-    if (impl == 0 || (K % 64) != 0) {
+    // (the matrix-core kernel stores whole 16-byte pieces of output rows; the SwiGLU one whole 64-wide chunks)
+    if (impl == 0 || (K % 64) != 0 || (N % 16) != 0 || ((epi == EPI_SWIGLU || epi == EPI_SWIGLU_RS) && (N % 64) != 0)) {
         if (dtype == KD_BF16) gemm_simt<bf16_t>(A, W, C, M, N, K, epi, sat, s);
         else gemm_simt<f16_t>(A, W, C, M, N, K, epi, sat, s);
         return 1;
