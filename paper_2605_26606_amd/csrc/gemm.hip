@@ -535,17 +535,42 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
         else CfgPrefill::run(A, W, C, M, N, K, epi, 1, sat, s);
         return 1;
     }
-    // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small
+    // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small.
+    // (Rules from sweeps of every configuration over the projection shapes of the 1.5B, 8B and 14B models at
+    // 128, 256 and 400 rows.)
     const bool can_split = slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32);
     const int nb128 = (N + 127) / 128;
+    // a long reduction amortises a block's fill and drain, and the tile with the most fragment reuse wins at
+    // every row count; a short one (the 1.5B model: 24 K tiles) prefers several smaller blocks per CU
+    const bool deep = K >= 3072;
     if (epi == EPI_SWIGLU || epi == EPI_SWIGLU_RS || nb128 >= 96) {   // wide outputs: no K slices needed
-        if (M > 384) CfgLarge3::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);       // four 128-row blocks, three per CU at a time
-        else if (M > 256) CfgLarge2::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);  // three 128-row blocks, not two of 256
+        if (M > 384 && !deep) CfgLarge3::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);       // four 128-row blocks, three per CU at a time
+        else if (M > 256 && !deep) CfgLarge2::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);  // three 128-row blocks, not two of 256
         else if (M > 128) CfgTall::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);    // a weight tile is fetched by exactly one block
         else CfgLarge::run(A, W, C, M, N, K, epi, 1, sat, s, row_scale);
         return 1;
     }
-    if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the feed-forward down projection)
+    if ((int64_t)N * K >= (int64_t)8 << 20 && nb128 >= 24) {
+        // mid-width outputs with large weights (q/k/v, o and down projections of the 8B / 14B models): 128-column
+        // tiles cut into about 240 blocks by K slices (8B down at 256 rows: 33 us against 48 us for 128x64 tiles)
+        if (M > 128) {
+            const int split = can_split ? CfgTall::pick_split(M, N, K, slice_cap_floats, 240) : 1;
+            if (split > 1) {
+                CfgTall::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
+                return split;
+            }
+            CfgTall::run(A, W, C, M, N, K, epi, 1, sat, s);
+            return 1;
+        }
+        const int split = can_split ? CfgLarge::pick_split(M, N, K, slice_cap_floats, 240) : 1;
+        if (split > 1) {
+            CfgLarge::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
+            return split;
+        }
+        CfgLarge::run(A, W, C, M, N, K, epi, 1, sat, s);
+        return 1;
+    }
+    if ((int64_t)N * K >= (int64_t)8 << 20) {   // narrow output, long K (the 1.5B model's down projection)
         if (M > 256) {
             const int split = can_split ? CfgMidTall::pick_split(M, N, K, slice_cap_floats, 240) : 1;
             if (split > 1) {

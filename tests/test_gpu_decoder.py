@@ -42,6 +42,10 @@ BF4 = workloads.scaled(C1, dtype="bf16", d_model=512, n_q_heads=8, n_kv_heads=2,
 # the head geometries of the 8B and 14B shapes: 8 kv heads with 4 and with 5 query heads each
 BF48 = workloads.scaled(C1, dtype="bf16", d_model=512, n_q_heads=32, n_kv_heads=8, head_dim=128, d_ff=1024,
                         vocab=2048, n_layers=2, rope_theta=1.0e6).model
+# projections as wide as the 8B model's (weights of 9 to 16 M elements per matrix, reductions of 3072 and more): the
+# decode GEMMs then take 128-column tiles cut into K slices, 128- or 256-row blocks by the batch
+BFW = workloads.scaled(C1, dtype="bf16", d_model=3072, n_q_heads=24, n_kv_heads=8, head_dim=128, d_ff=4096,
+                       vocab=2048, n_layers=1, rope_theta=1.0e6).model
 BF58 = workloads.scaled(C1, dtype="bf16", d_model=640, n_q_heads=40, n_kv_heads=8, head_dim=128, d_ff=1024,
                         vocab=2048, n_layers=2, rope_theta=1.0e6).model
 
@@ -196,6 +200,9 @@ def test_bf16_plain_alu_path():
     (BF48, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 32 query / 8 kv heads
     (BF58, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 40 query / 8 kv heads: 5 per kv head, one head per prefill wave
     (BF58, [20] * 40, 4, 5, 64, 0.02, "bf16"),            # 160 rows x 8 kv heads: the 4-wave decode blocks
+    (BFW, [10] * 20 + [37], 4, 4, 64, 0.02, "f16"),       # 84 rows: 128x128 tiles in K slices
+    (BFW, [10] * 40 + [37], 4, 4, 64, 0.02, "f16"),       # 164 rows: 256x128 tiles in K slices
+    (BFW, [9] * 70, 4, 4, 64, 0.02, "f16"),               # 280 rows: two 256-row blocks per weight tile
 ])
 def test_bf16_matrix_core_path(model, lens, G, T, bs, std, act):
     say("bf16 model, matrix-core path, %s activations, lens=%s G=%d T=%d std=%g" % (act, lens[:6], G, T, std))
