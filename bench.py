@@ -160,7 +160,7 @@ def main():
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of one sequence of the workload")
-    ap.add_argument("--verbose", action="store_true", help="report each phase on stderr as it completes")
+    ap.add_argument("--verbose", action="store_true", help="(kept for old command lines: phases are always reported on stderr)")
     ap.add_argument("--eos-bias", default="0",
                     help="logit bias on the EOS id of the workloads that stop on EOS: a number, or 'ragged' for "
                          "ln(V / (T/2)), i.e. a stop hazard of about 2/T per step (mean length near T/2); "
@@ -169,6 +169,9 @@ def main():
                     help="cap on the prompts committed per step (Section 3.3 b_t); also bounds the KV pool, which "
                          "otherwise is sized for every prompt being kept")
     ap.add_argument("--time-every", type=int, default=64)
+    ap.add_argument("--act", default="f16", choices=["f16", "bf16"],
+                    help="activation / KV type of 16-bit models: IEEE half (the accepted configuration) or bfloat16 "
+                         "(outside the 2e-2 logit bound at 28 layers; measured for comparison)")
     ap.add_argument("--no-graph", action="store_true",
                     help="launch decode steps eagerly (for counter runs: the profiler's counter mode and HIP graphs "
                          "do not go together)")
@@ -227,7 +230,8 @@ def main():
             pool / 2 ** 30, want_pool / 2 ** 30)
         sys.stderr.write("[bench] " + say_early + "\n")
     ctx = pc.Context(m, w, block_size=64, kv_pool_bytes=pool,
-                     max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=rows_max)
+                     max_slots=n_prompts_alive + n_max + 8, max_ctx=Lp + T + 64, max_batch_rows=rows_max,
+                     act_dtype=args.act)
     if args.no_graph:
         pc.pc_set_option(ctx, pc.PC_OPT_USE_GRAPH, 0)
     cu = (np.arange(P + 1) * Lp).astype(np.int32)
@@ -241,10 +245,9 @@ def main():
         if wl.reward == "bernoulli" else None
     stream = torch.cuda.Stream()
 
-    def say(msg):
-        if args.verbose:
-            sys.stderr.write("[bench %.0f s] %s\n" % (time.perf_counter() - t_start, msg))
-            sys.stderr.flush()
+    def say(msg):   # a line per completed phase on stderr (a long workload is silent for minutes otherwise)
+        sys.stderr.write("[bench %.0f s] %s\n" % (time.perf_counter() - t_start, msg))
+        sys.stderr.flush()
 
     t_start = time.perf_counter()
 
@@ -281,8 +284,8 @@ def main():
         achieved = attn_bytes / attn_launches / (avg_ms * 1e-3) / 1e9
         pilot_t = [t for (which, t, _, _) in timed_steps if which == "pilot"]
         traffic = counter_traffic_bytes(P * wl.n_pilot, Lp, sum(pilot_t) / max(1, len(pilot_t))) \
-            if len(pilot_t) == len(timed_steps) else None
-        roof = {"kernel": "attention_decode_mfma_kernel<f16, direct, 4 waves> (pilot pass, %d sequences)" % (P * wl.n_pilot), "bound": "hbm", "achieved": round(achieved, 1),
+            if len(pilot_t) == len(timed_steps) and args.act == "f16" else None
+        roof = {"kernel": "attention_decode_mfma_kernel<%s, direct, 4 waves> (pilot pass, %d sequences)" % (args.act, P * wl.n_pilot), "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(avg_ms * 1e3, 2), "event_bracket_us": round(bracket_ms * 1e3, 2),
                 "launches_timed": int(attn_launches),
@@ -308,7 +311,7 @@ def main():
         "ms_per_step": round(dt * 1e3 / max(1, args.steps), 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         # matrix-core inputs: IEEE half copies of the bf16 weights and half activations / KV, fp32 accumulation
-        "dtype": "f16" if m.dtype == "bf16" else m.dtype, "data": "synthetic",
+        "dtype": args.act if m.dtype == "bf16" else m.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d prompts x %d tokens, pilot %d + commit %d rollouts on kept prompts, %d new "
                                "tokens, L%d d%d %dq/%dkv hd%d ff%d V%d, random init" %
                                (wl.name, P, Lp, wl.n_pilot, wl.n_commit, T, m.n_layers, m.d_model, m.n_q_heads,
@@ -317,10 +320,11 @@ def main():
                    "kv_pool_GB": round(pool / 2 ** 30, 1),
                    "kept_prompts": [int(o["counts"][0]) for o in outs],
                    "rollouts": [int(o["rollouts"]) for o in outs]},
-        "roofline": roof,
+        # the whole decode loop first, then its dominant kernel
         "decode": {"ms": round(dec_ms, 1), "steps": sum(o["decode_steps"] for o in outs),
                    "algorithmic_GBps": None if ragged else round(dec_bytes / max(dec_ms, 1e-9) / 1e6, 1),
                    "frac_hbm": None if ragged else round(dec_bytes / max(dec_ms, 1e-9) / 1e6 / HBM_PEAK_GBPS, 4)},
+        "roofline": roof,
         "prefill": {"ms": round(prefill_ms, 2), "TFLOPs": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9, 1),
                     "frac_mfma": round(prefill_flops / max(prefill_ms, 1e-9) / 1e9 / MFMA_BF16_PEAK_TFLOPS, 4)},
     }
@@ -343,6 +347,7 @@ def main():
                 marks.append(time.perf_counter())
                 if o is not None:
                     info.append((o["rows"], o["tokens_generated"], marks[-1] - marks[-2]))
+                    say("bound pipeline: pass %d done (%d rows)" % (len(info), o["rows"]))
             pipe.close()
         tot_tok = sum(i[1] for i in info)
         mid = info[1:-1] if len(info) > 2 else info
@@ -380,6 +385,7 @@ def main():
                              "rows": rows_s, "ms": round(dt_s * 1e3, 1), "TFLOPs": round(flops / dt_s / 1e12, 1),
                              "frac_mfma": round(flops / dt_s / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4),
                              "mean_logprob": round(float(lp_out.mean().item()), 4)}
+        say("scoring pass done")
     if not args.no_gemm_timing:
         # per-launch time of the decode step's projection GEMMs at the pilot batch size (outside the timed region):
         # a few eagerly launched decode steps with an event pair around every launch of one class, as for the
@@ -407,6 +413,7 @@ def main():
                 us = max(ms / cnt - (ems / ecnt if ecnt else 0.0), 1e-6) * 1e3
                 byts = 2.0 * N * K + 2.0 * n * K + float(out_bytes) * n * N
                 flops = 2.0 * n * N * K
+                say("decode GEMM timing: %s done" % name)
                 gem[name] = {"us": round(us, 2), "launches_timed": int(cnt), "GBps": round(byts / us / 1e3, 1),
                              "frac_hbm": round(byts / us / 1e3 / HBM_PEAK_GBPS, 4), "TFLOPs": round(flops / us / 1e6, 1),
                              "frac_mfma": round(flops / us / 1e6 / MFMA_BF16_PEAK_TFLOPS, 4)}
@@ -420,6 +427,7 @@ def main():
         del src, dst
     if not args.no_parity and eos_id < 0 and m.dtype == "bf16":
         result["parity"] = parity_sample(pc, ctx, wl, w, toks, cu, prompts, uids, wl.seed_sampler + 5, stream)
+        say("parity sample done")
     result["saturated_stores"] = pc.pc_saturation_count(ctx)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, w, prompts, uids, wl.seed_sampler)
