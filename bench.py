@@ -111,14 +111,17 @@ def cpu_baseline(wl, w_dev, prompts, uids, seed):
     return out
 
 
-def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream):
-    """One pilot sequence of a fresh pilot pass, teacher-forced through the oracle at 12 steps spread over the context:
-    max-abs logit error and the two token agreements (the oracle's sampler on the GPU's logits / on its own)."""
+def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream, span=0, say=None):
+    """One pilot sequence of a fresh pilot pass, teacher-forced through the oracle at 12 steps spread over the context
+    (over its first `span` generated tokens when span > 0: the oracle's cost grows with the context, and for the
+    8B shape the whole one takes it a quarter of an hour): max-abs logit error and the two token agreements (the
+    oracle's sampler on the GPU's logits / on its own)."""
     import numpy as np
     import torch
     from oracle import decoder, philox, sampler
     m, P, Lp, T = wl.model, wl.n_prompts, wl.prompt_len, wl.new_tokens
-    steps = sorted(set([0, 1, T - 1] + np.linspace(2, T - 2, 9).astype(int).tolist()))
+    Ts = min(T, span) if span > 0 else T
+    steps = sorted(set([0, 1, Ts - 1] + np.linspace(2, Ts - 2, 9).astype(int).tolist()))
     seq = wl.n_pilot * (P // 2) + 1
     with torch.cuda.stream(stream):
         last = torch.empty((P, m.vocab), dtype=torch.float32, device=toks.device)
@@ -132,8 +135,9 @@ def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream):
     gen = g["tokens"][seq].cpu().numpy()
     gl = {t: lg[0].cpu().numpy() for t, lg in zip(g["logits_steps"], g["logits"])}
     w_cpu = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in w_dev.items()}
-    full = np.concatenate([prompts[rows[seq]], gen])
-    want = decoder.forward_full(m, w_cpu, full[:-1], rows=[Lp - 1 + t for t in steps])
+    full = np.concatenate([prompts[rows[seq]], gen[:Ts]])
+    want = decoder.forward_full(m, w_cpu, full[:-1], rows=[Lp - 1 + t for t in steps],
+                                on_layer=(lambda l: say("oracle: layer %d of %d" % (l + 1, m.n_layers))) if say else None)
     worst = sq = 0.0
     same = own = 0
     for a, t in enumerate(steps):
@@ -143,7 +147,8 @@ def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream):
         u = philox.sampling_uniform(seed, int(seq_uids[seq]), t)
         same += int(sampler.sample_token(gl[t], wl.temperature, u)[0] == gen[t])
         own += int(sampler.sample_token(want[a], wl.temperature, u)[0] == gen[t])
-    return {"positions": len(steps), "max_abs_logit_error": round(worst, 5),
+    return {"positions": len(steps), "context": "%d prompt + first %d generated tokens" % (Lp, Ts),
+            "max_abs_logit_error": round(worst, 5),
             "rms_logit_error": round(float(np.sqrt(sq / len(steps))), 6),
             "tokens_from_gpu_logits": same, "tokens_from_oracle_logits": own,
             "note": "one pilot sequence of the timed workload, teacher-forced through the float64 oracle; agreement from "
@@ -160,6 +165,8 @@ def main():
     ap.add_argument("--new-tokens", type=int, default=0, help="override the workload's new tokens (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parity", action="store_true", help="skip the oracle check of one sequence of the workload")
+    ap.add_argument("--parity-span", type=int, default=0,
+                    help="check only the first N generated tokens of that sequence (large models: the oracle is slow)")
     ap.add_argument("--verbose", action="store_true", help="(kept for old command lines: phases are always reported on stderr)")
     ap.add_argument("--eos-bias", default="0",
                     help="logit bias on the EOS id of the workloads that stop on EOS: a number, or 'ragged' for "
@@ -426,7 +433,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_parity and eos_id < 0 and m.dtype == "bf16":
-        result["parity"] = parity_sample(pc, ctx, wl, w, toks, cu, prompts, uids, wl.seed_sampler + 5, stream)
+        result["parity"] = parity_sample(pc, ctx, wl, w, toks, cu, prompts, uids, wl.seed_sampler + 5, stream,
+                                         span=args.parity_span, say=say if m.n_layers * m.d_model > 28 * 1536 else None)
         say("parity sample done")
     result["saturated_stores"] = pc.pc_saturation_count(ctx)
     if not args.no_cpu_baseline:

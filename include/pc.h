@@ -104,10 +104,12 @@ typedef struct {
 /* Options for pc_set_option. */
 #define PC_OPT_USE_GRAPH 1   /* 1: replay the decode step as a HIP graph (default 1) */
 #define PC_OPT_FORCE_SIMT 2  /* 1: plain-ALU kernels also for bf16 (debugging aid; default 0) */
-#define PC_OPT_FUSE_DECODE 4   /* 1: decode batches of up to 512 rows of a 16-bit model run the fused layer (q/k/v projection
-                                  with rotary positions and cache append in its epilogue; output projection that also
-                                  leaves the next RMSNorm's inputs; that norm's scale applied by the gate/up epilogue): six
-                                  launches per layer instead of eight (default 1; 0 keeps one kernel per operation) */
+#define PC_OPT_FUSE_DECODE 4   /* 1: decode batches of up to 512 rows of a 16-bit model with head_dim 128 whose q/k/v
+                                  projection has at most 8 M weights run the fused layer (q/k/v projection with rotary
+                                  positions and cache append in its epilogue; output projection that also leaves the next
+                                  RMSNorm's inputs; that norm's scale applied by the gate/up epilogue): six launches per
+                                  layer instead of eight; larger models keep one kernel per operation, which is faster
+                                  there (default 1; 0 keeps one kernel per operation everywhere) */
 #define PC_OPT_TIME_NEXT_STEP 3 /* value = a PC_KERNEL_* class: the next pc_decode_step runs eagerly (no graph)
                                    with a HIP event pair around every launch of that class; -1 disarms */
 

@@ -132,15 +132,18 @@ def _logits(shape, w, h, dtype):
     return rmsnorm(h, _np(w["final_norm"], dtype), shape.rms_eps) @ _np(w["lm_head"], dtype).T
 
 
-def forward_full(model, w, tokens, dtype=np.float64, rows=None):
+def forward_full(model, w, tokens, dtype=np.float64, rows=None, on_layer=None):
     """Brute force: logits for the whole sequence `tokens` [L] (or only for
-    the positions listed in `rows`), recomputed from scratch."""
+    the positions listed in `rows`), recomputed from scratch.  `on_layer(l)`,
+    if given, is called after each layer (progress reports of long runs)."""
     s = Shape(model)
     tokens = np.asarray(tokens, dtype=np.int64)
     pos = np.arange(len(tokens))
     h = _embed(w, tokens, dtype)
     for l in range(s.n_layers):
         h, _, _ = _layer(s, w, l, h, pos, None, None, dtype)
+        if on_layer is not None:
+            on_layer(l)
     if rows is not None:
         h = h[np.asarray(rows)]
     return _logits(s, w, h, dtype)

@@ -265,7 +265,8 @@ int enqueue_layers(pc_ctx *ctx, int rows, const int32_t *row_slot, const int32_t
     const bool fused = !row_pos && ctx->fuse_decode && impl == 1 && ctx->mfma_attention() && ctx->qkv_perm &&
                        skinny_ok(rows, qd + 2 * kvd, m.d_model, m.head_dim) &&
                        skinny_ok(rows, m.d_model, qd, m.head_dim) &&
-                       (int64_t)(qd + 2 * kvd) * m.d_model <= ((int64_t)8 << 20);
+                       (int64_t)(qd + 2 * kvd) * m.d_model <= ((int64_t)8 << 20) &&
+                       (2 * m.d_ff) % 64 == 0;   // the gate/up epilogue with the norm scale exists on the matrix-core kernel only
     for (int l = 0; l < m.n_layers; ++l) {
         launch_rmsnorm(dt, ctx->h, nullptr, ctx->attn_norm[l], rows, m.d_model, m.rms_eps, ctx->a, ctx->cur_slices, pending,
                        sat, st);

@@ -2,8 +2,9 @@
 //   C[M,N] = A[M,K] * W[N,K]^T, fp32 accumulation, with fused epilogues.
 // Two implementations:
 //   gemm_simt   plain-ALU tiles, any dtype (the fp32 model path)
-//   gemm_mfma   bf16 on the matrix cores (v_mfma_f32_32x32x16_bf16), LDS
-//               double-buffered, one barrier per K tile
+//   gemm_mfma   bf16 / f16 on the matrix cores (32x32x16 or 16x16x32 products),
+//               operands streamed global -> LDS several K tiles ahead, one
+//               barrier per K tile, output rows re-formed through LDS
 #include <algorithm>
 
 #include <type_traits>
