@@ -116,7 +116,7 @@ static constexpr int N_XCD = 8;   // MI355X: 8 accelerator dies, each with its o
 // slice order (no atomics, no fences: the kernel boundary orders the two).
 //
 // Data path: global memory -> LDS directly (global_load_lds_dwordx4, no register staging), NSTAGE
-// tiles deep, one barrier per K tile.  A wave-wide load lands as 1 KB of consecutive LDS (8 rows of
+// tiles deep, one barrier per K tile; LDS -> registers one K step ahead of the products, also across tiles.  A wave-wide load lands as 1 KB of consecutive LDS (8 rows of
 // 64 k); to keep the 128-bit fragment reads conflict free without padding, the 16-byte chunk c of
 // row r is stored at chunk slot c ^ swz(r) (the lane fetches the chunk its slot must hold), where swz
 // makes any 16 consecutive rows hit 16 different 16-byte bank groups.  K must be a multiple of 64 here.
@@ -152,14 +152,31 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
     static_assert(BK == 64 || BK == 32, "K tile");
     static_assert(BM % (RPL * NW) == 0 && BN % (RPL * NW) == 0, "whole passes");
     static_assert(!SWIGLU || (BN / WN) % 64 == 0, "SwiGLU needs whole 64-wide gate/up chunks per wave");
-    static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt is a 6-bit counter");
+    static_assert(NSTAGE * LOADS <= 63, "vmcnt is a 6-bit counter");
     extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
     T *smem = (T *)smem_raw;                     // [NSTAGE][A tile BM x 64 | W tile BN x 64]
 
     // ---- which tile
     const int id = blockIdx.x;
     int bm, bn, z;
-    if (plain) {   // many row blocks (prefill): neighbours share the activation rows, plain order
+    if (plain == 2) {
+        // many row blocks, a multiple of 8 (prefill): every die owns mb/8 row blocks and walks all column blocks in
+        // groups of 8, patch by patch of 4 row blocks x 8 column blocks.  The 32 blocks a die runs at a time then
+        // share 4 activation slabs and 8 weight slabs (its L2 serves each K tile to 8 resp. 4 blocks), where plain
+        // order gave a die 32 different weight slabs at once.
+        const int die = id % N_XCD, j = id / N_XCD;
+        const int rows_per = mb / N_XCD;
+        if (j >= rows_per * nb) return;
+        const int ph = (rows_per % 4 == 0) ? 4 : ((rows_per % 2 == 0) ? 2 : 1);
+        const int full = rows_per * 8;                        // tiles of a full group of 8 column blocks
+        const int cg = min(j / full, (nb - 1) / 8);
+        const int w = min(8, nb - 8 * cg);
+        const int jj = j - cg * full;
+        const int sg = jj / (ph * w), r = jj % (ph * w);
+        bm = die * rows_per + sg * ph + r % ph;
+        bn = 8 * cg + r / ph;
+        z = 0;
+    } else if (plain) {   // many row blocks (prefill): neighbours share the activation rows, plain order
         bn = id % nb;
         bm = id / nb;
         z = 0;
@@ -214,18 +231,18 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
                                              (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
     };
 
-    auto issue_part = [&](int kt, int stage, int l) {     // load l of the tile (l < A_ITERS: operand A)
-        const int koff = min(kt, kt1 - 1) * BK;
+    auto issue_part = [&](int kt, int stage, int part, int parts) {   // the loads l of a tile with l * parts / LOADS == part
+        const int koff = min(kt, kt1 - 1) * BK;            // past the end: a redundant reload, keeps the count constant
         T *sa = smem + stage * STAGE_ELEMS;
         T *sw = sa + BM * BK;
 #pragma unroll
         for (int i = 0; i < A_ITERS; ++i)
-            if (i == l)
+            if (i * parts / LOADS == part)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pa[i] + koff),
                                                  (__attribute__((address_space(3))) void *)(sa + (NW * i + wave) * RPL * BK), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < W_ITERS; ++i)
-            if (A_ITERS + i == l)
+            if ((A_ITERS + i) * parts / LOADS == part)
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(pw[i] + koff),
                                                  (__attribute__((address_space(3))) void *)(sw + (NW * i + wave) * RPL * BK), 16, 0, 0);
     };
@@ -261,39 +278,71 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
         if constexpr (M16) return Mma<T>::m16(a, b, c);
         else return Mma<T>::m32(a, b, c);
     };
-    auto compute = [&](int stage, int kt_next, int refill) {
+    // One K step (the products of 8*CG k values of every accumulator tile), software-pipelined ACROSS K tiles: while
+    // the products of this step run on the fragments `ca`/`cb` already in registers, the fragments of the next step
+    // are read into `na`/`nb` -- the next step of the same tile, or, in a tile's last step, the first step of the next
+    // tile.  That read needs the next tile visible, so the block's one barrier per tile sits in front of the last
+    // step (not at the top of the tile), and right behind it the stage just consumed is refilled.  No product then
+    // waits for an LDS read issued just before it (the first version did, once per tile: with one step per tile the
+    // matrix cores idled half the time).
+    // Wave tiles of fewer than four accumulator tiles (the 128x64 and 64x64 blocks of the small decode projections)
+    // keep the barrier at the top of the tile and prefetch within the tile only: with two products per step there
+    // is nothing to hide the hand-over under, and the plain order measured faster there (decode down projection
+    // 15.1 against 16.5 us).
+    constexpr int KK = BK / (8 * CG);                     // steps per tile
+    constexpr bool XT = (TM * TN >= 4);                   // pipelined across tiles
+    auto kstep = [&](frag_t (&ca)[TM], frag_t (&cb)[TN], frag_t (&na)[TM], frag_t (&nb)[TN], int kt, int stage, int kk) {
         const T *sa = smem + stage * STAGE_ELEMS;
         const T *sw = sa + BM * BK;
-        frag_t fa[2][TM], fb[2][TN];                       // fragments of step kk+1 are fetched under the products of step kk
-        load_frags(sa, sw, 0, fa[0], fb[0]);
-        constexpr int KK = BK / (8 * CG);
-#pragma unroll
-        for (int kk = 0; kk < KK; ++kk) {
-            // this step's share of the refill: the loads are spread over the tile's compute steps
-#pragma unroll
-            for (int l = 0; l < LOADS; ++l)
-                if (l * KK / LOADS == kk) issue_part(kt_next, refill, l);
-            if (kk + 1 < KK) load_frags(sa, sw, kk + 1, fa[(kk + 1) & 1], fb[(kk + 1) & 1]);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int jj = 0; jj < TN; ++jj)
-                    acc[i][jj] = product(fb[kk & 1][jj], fa[kk & 1][i], acc[i][jj]);   // weights as rows: the tile comes out transposed
-            // instruction order asked of the compiler: after each matrix instruction one or two LDS fragment
-            // reads and one global->LDS load, instead of all reads in a burst behind the last product
-            // (measured: +5 % on the prefill shapes, neutral on the decode shapes)
-#pragma unroll
-            for (int g = 0; g < TM * TN; ++g) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, (TM + TN + TM * TN - 1) / (TM * TN), 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        const int pstage = (stage == 0) ? NSTAGE - 1 : stage - 1;
+        if constexpr (!XT) {
+            if (kk == 0) {
+                wait_vmcnt_le<(NSTAGE - 2) * LOADS>();    // this thread's loads of tile kt have landed
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();             // ... and everybody's; tile kt-1 is consumed
+                asm volatile("" ::: "memory");
+                load_frags(sa, sw, 0, ca, cb);
             }
+            issue_part(kt - 1 + NSTAGE, pstage, kk, KK);  // the refill of tile kt-1's stage, spread over the steps
+            if (kk + 1 < KK) load_frags(sa, sw, kk + 1, na, nb);
+        } else if (kk == KK - 1) {
+            wait_vmcnt_le<(NSTAGE - 2) * LOADS>();        // this thread's loads of tile kt+1 have landed
+            __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): and its own reads of tile kt have returned
+            // ... and everybody's: behind the barrier tile kt+1 is visible and tile kt's stage is free.  A bare
+            // barrier: __syncthreads() would add a fence that drains every load in flight.
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const int nstage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+            issue_part(kt + NSTAGE, stage, 0, KK);        // the refill of the stage just consumed starts here ...
+            const T *nsa = smem + nstage * STAGE_ELEMS;
+            load_frags(nsa, nsa + BM * BK, 0, na, nb);    // (behind the last tile: read and never used)
+        } else {
+            // ... and goes on over the next tile's other steps (a wave that has to hand the load unit six loads
+            // in a row cannot issue matrix instructions meanwhile)
+            issue_part(kt - 1 + NSTAGE, pstage, kk + 1, KK);
+            load_frags(sa, sw, kk + 1, na, nb);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int jj = 0; jj < TN; ++jj)
+                acc[i][jj] = product(cb[jj], ca[i], acc[i][jj]);   // weights as rows: the tile comes out transposed
+        // instruction order asked of the compiler: after each matrix instruction one or two LDS fragment reads and
+        // one global->LDS load, instead of all of them in a burst
+#pragma unroll
+        for (int g = 0; g < TM * TN; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, (TM + TN + TM * TN - 1) / (TM * TN), 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
     };
 
-    // tile kt lives in stage (kt - kt0) % NSTAGE; NSTAGE-1 tiles are in flight
+    // tile kt lives in stage (kt - kt0) % NSTAGE; the tile being consumed sits in registers, the next one in LDS,
+    // NSTAGE-1 more are in flight
 #pragma unroll
     for (int s = 0; s < NSTAGE - 1; ++s) issue_tile(kt0 + s, s);
+    if constexpr (XT) issue_part(kt0 + NSTAGE - 1, NSTAGE - 1, 0, KK);   // (its other parts: the first tile's steps)
     // (behind the first tile loads, so that the pipeline is already filling while the statistics arrive; these are
     // ordinary loads, younger than the tile loads: once they are back, so are the tiles)
     if constexpr (EPI == EPI_SWIGLU_RS) {
@@ -319,18 +368,35 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
         if (part == 0) s_rs[r] = 1.0f / sqrtf(ss / (float)rsc.d + rsc.eps);
         __syncthreads();
     }
-    int stage = 0;
-    for (int kt = kt0; kt < kt1; ++kt) {
-        wait_vmcnt_le<(NSTAGE - 2) * LOADS>();             // this thread's loads of tile kt have landed
-        // ... and everybody's; tile kt-1 is fully consumed (its fragment reads were waited for before the
-        // matrix-core instructions that used them).  A bare barrier: __syncthreads() would add a fence that
-        // drains every load in flight.
+    frag_t fa[2][TM], fb[2][TN];
+    if constexpr (XT) {
+        constexpr int PART0 = (LOADS + KK - 1) / KK;       // loads l with l * KK / LOADS == 0
+        wait_vmcnt_le<(NSTAGE - 2) * LOADS + PART0>();     // the first tile has landed
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        const int refill = (stage == 0) ? NSTAGE - 1 : stage - 1;
-        compute(stage, kt + NSTAGE - 1, refill);
-        stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+        load_frags(smem, smem + BM * BK, 0, fa[0], fb[0]);
+    }
+    int stage = 0;
+    if constexpr (KK % 2 == 0) {   // an even number of steps per tile: the two fragment sets alternate within a tile
+        for (int kt = kt0; kt < kt1; ++kt) {
+#pragma unroll
+            for (int kk = 0; kk < KK; kk += 2) {
+                kstep(fa[0], fb[0], fa[1], fb[1], kt, stage, kk);
+                kstep(fa[1], fb[1], fa[0], fb[0], kt, stage, kk + 1);
+            }
+            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+        }
+    } else {                       // one step per tile: they alternate from tile to tile
+        static_assert(KK == 1 || KK % 2 == 0, "steps per tile");
+        int kt = kt0;
+        for (; kt + 1 < kt1; kt += 2) {
+            kstep(fa[0], fb[0], fa[1], fb[1], kt, stage, 0);
+            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+            kstep(fa[1], fb[1], fa[0], fb[0], kt + 1, stage, 0);
+            stage = (stage + 1 == NSTAGE) ? 0 : stage + 1;
+        }
+        if (kt < kt1) kstep(fa[0], fb[0], fa[1], fb[1], kt, stage, 0);
     }
     wait_vmcnt_le<0>();   // nothing may still be writing LDS when the block retires
 
@@ -445,7 +511,7 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64, b
         const GemmRowScale rsc = row_scale ? *row_scale : GemmRowScale{nullptr, 0, 1, 0.f};
         const int mb = (M + BM - 1) / BM, nb = (N + BN - 1) / BN;
         const int units = nb * split;
-        const int plain = (split == 1 && mb > 4) ? 1 : 0;
+        const int plain = (split == 1 && mb > 4) ? ((mb % N_XCD == 0) ? 2 : 1) : 0;
         const unsigned grid = plain ? (unsigned)(mb * nb) : (unsigned)((units + N_XCD - 1) / N_XCD * N_XCD * mb);
         const T *a = (const T *)A, *w = (const T *)W;
         switch (epi) {
@@ -478,7 +544,7 @@ template <typename T, int BM, int BN, int WM, int WN, int NSTAGE, int BK = 64, b
 
 template <typename T> static void gemm_init_t() {
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
-    MfmaCfg<T, 256, 256, 4, 2, 3, 32, true>::init();
+    MfmaCfg<T, 256, 256, 4, 2, 4, 32, true>::init();
     MfmaCfg<T, 256, 128, 4, 2, 3, 64, true>::init();
     MfmaCfg<T, 128, 128, 2, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
@@ -521,7 +587,7 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     // prefill: 16x16x32 products (measured +3 to +12 % over 32x32x16 at 16384 rows, nothing at decode sizes;
     // the results are bit-identical)
     typedef MfmaCfg<T, 256, 128, 4, 2, 3, 64, true> CfgPrefill;
-    typedef MfmaCfg<T, 256, 256, 4, 2, 3, 32, true> CfgWide;   // wave tile 64x128: three fragment reads per four products
+    typedef MfmaCfg<T, 256, 256, 4, 2, 4, 32, true> CfgWide;   // wave tile 64x128: three fragment reads per four products
     typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
     typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 128, 128, 2, 2, 3, 32> CfgLarge3;    // BK 32, 48 KB of LDS: three blocks per CU

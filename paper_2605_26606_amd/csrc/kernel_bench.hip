@@ -185,7 +185,7 @@ static int bench_gemm() {
     rc |= run_gemm<MfmaCfg<T, 128, 64, 2, 2, 4>>("decode down", 256, 1536, 8960, EPI_STORE_F32, 5, Ws, A, C, slices);
     rc |= run_gemm<MfmaCfg<T, 64, 64, 2, 2, 4>>("decode o-proj", 256, 1536, 1536, EPI_STORE_F32, 2, Ws, A, C, slices);
     rc |= run_gemm<MfmaCfg<T, 64, 64, 2, 2, 4>>("decode qkv", 256, 2048, 1536, EPI_STORE_F32, 2, Ws, A, C, slices);
-    rc |= run_gemm<MfmaCfg<T, 256, 256, 4, 2, 3, 32, true>>("prefill gate/up (SwiGLU)", 16384, 17920, 1536, EPI_SWIGLU, 1, Ws, A, C, slices);
+    rc |= run_gemm<MfmaCfg<T, 256, 256, 4, 2, 4, 32, true>>("prefill gate/up (SwiGLU)", 16384, 17920, 1536, EPI_SWIGLU, 1, Ws, A, C, slices);
     rc |= run_gemm<MfmaCfg<T, 256, 128, 4, 2, 3, 64, true>>("prefill down (+residual)", 16384, 1536, 8960, EPI_RESID_F32, 1, Ws, A, C, slices);
     return rc;
 }
