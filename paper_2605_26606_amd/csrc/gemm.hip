@@ -598,8 +598,21 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
         // 256x256 tiles where they still come in several rounds per CU (the wide projections: +10 % measured);
         // the narrow ones (1536 columns: 1.5 rounds of such tiles) keep 256x128
         const int64_t wide_tiles = (int64_t)((M + 255) / 256) * ((N + 255) / 256);
-        if (wide_tiles >= 2 * 256) CfgWide::run(A, W, C, M, N, K, epi, 1, sat, s);
-        else CfgPrefill::run(A, W, C, M, N, K, epi, 1, sat, s);
+        if (wide_tiles >= 2 * 256) {
+            CfgWide::run(A, W, C, M, N, K, epi, 1, sat, s);
+            return 1;
+        }
+        // a large decode batch (a thousand rows) against a narrow projection leaves most CUs without a tile
+        // (1024 rows x 1536 columns: 48 tiles of 256x128): cut K into slices, as the small batches do
+        const int64_t tiles = (int64_t)((M + 255) / 256) * ((N + 127) / 128);
+        if (tiles < 160 && slices && (epi == EPI_STORE_F32 || epi == EPI_RESID_F32)) {
+            const int split = CfgPrefill::pick_split(M, N, K, slice_cap_floats, 240);
+            if (split > 1) {
+                CfgPrefill::run(A, W, slices, M, N, K, EPI_STORE_F32, split, sat, s);
+                return split;
+            }
+        }
+        CfgPrefill::run(A, W, C, M, N, K, epi, 1, sat, s);
         return 1;
     }
     // decode: the weights are streamed once; fill the chip with blocks, by K slices where N is small.

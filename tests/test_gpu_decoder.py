@@ -195,6 +195,7 @@ def test_bf16_plain_alu_path():
     (BF8, [100, 31], 3, 10, 64, 0.02, "bf16"),
     (BF8, [12] * 75, 4, 5, 64, 0.02, "f16"),              # 300 decode rows: 128-row GEMM blocks in threes, tall K slices
     (BF8, [12] * 105, 4, 4, 64, 0.02, "f16"),             # 420 decode rows: four 128-row blocks, BK 32
+    (BF8, [12] * 130, 4, 3, 64, 0.02, "f16"),             # 520 decode rows: the large-batch tiles, narrow outputs in K slices
     (BF, [70, 33, 300, 5, 256], 3, 10, 128, 0.02, "f16"), # larger KV blocks
     (BF, [70, 33, 300, 5, 256], 3, 10, 256, 0.02, "f16"), # the largest block size the cache accepts
     (BF48, [150, 9, 64, 257], 4, 12, 64, 0.02, "f16"),    # 32 query / 8 kv heads
