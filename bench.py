@@ -192,7 +192,7 @@ def main():
                     help="also run one plain 1 GiB device copy (the known-size reference of the counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.stderr.write("bench.py: this build runs on one GPU; --gpus %d is not supported (no multi-GPU path "
+        sys.stderr.write("bench.py: this library runs on one GPU; --gpus %d is not supported (no multi-GPU path "
                          "exists in this library)\n" % args.gpus)
         sys.exit(2)
 

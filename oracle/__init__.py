@@ -14,7 +14,7 @@ Modules
               restricted to the nucleus (top-p; Section 4.2 names the parameter)
   allocation  group statistics (Eq. 3), pilot filter / eviction / commit set
               (Section 3.3, Algorithm 1), the variance form of the filter for non-binary
-              rewards (Section 3.3's remark on the extension; the rule is this build's reading),
+              rewards (Section 3.3's remark on the extension; the rule is this implementation's reading),
               group-relative advantages, sampling cost (Section 4.3)
   scheduler   multi-step scheduling: replay buffer, maximum delay, eviction (Algorithm 1,
               Section 3.4)

@@ -13,7 +13,7 @@ pc_advantages.
   select_commit_variance
                   the same filter on the group variance itself, for rewards
                   that are not binary (Introduction, Section 3.3, Section 7:
-                  the paper names the extension, the rule is this build's
+                  the paper names the extension, the rule is this implementation's
                   reading)
   advantages      Section 3.1: A_i = (r_i - mu) / sigma over the union of a
                   kept prompt's pilot and commit rollouts (Section 3.3,

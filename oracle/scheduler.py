@@ -20,7 +20,7 @@ counter t.
       dropped, and t <- t + 1.
 
 Readings where the paper leaves the choice open (each also listed with the
-other readings of this build):
+other readings of this implementation):
   * order of selection from R ("sample prompt q from R"): the survivors of
     the current step first, in batch order (Section 3.4: only the EXCESS of
     a step goes to the buffer, and the buffer is drawn on when the current

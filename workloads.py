@@ -97,8 +97,8 @@ WORKLOADS: Dict[str, Workload] = {
     "C3": Workload("C3", _QWEN15, 128, 512, 8, 8, 2048, reward="last_mod7", eos=True),
     "C4": Workload("C4", _QWEN8, 64, 512, 4, 12, 2048, reward="bernoulli"),
     "C5": Workload("C5", _QWEN14, 32, 1024, 4, 12, 4096, reward="bernoulli", eos=True),
-    # the 1.5B stress shape with the paper's evaluation sampling (Section 4.2: temperature 0.7; top-p is this
-    # build's addition: 0.95) and a four-valued reward selected on by the variance filter
+    # the 1.5B stress shape with the paper's evaluation sampling (Section 4.2: temperature 0.7; top-p is an
+    # addition here: 0.95) and a four-valued reward selected on by the variance filter
     "C3E": Workload("C3E", _QWEN15, 128, 512, 8, 8, 2048, temperature=0.7, top_p=0.95, reward="graded_mod7",
                     filter="variance", var_hard=0.02, var_easy=0.05, eos=True),
 }
