@@ -546,7 +546,7 @@ template <typename T> static void gemm_init_t() {
     MfmaCfg<T, 256, 128, 4, 2, 3>::init();
     MfmaCfg<T, 256, 256, 4, 2, 4, 32, true>::init();
     MfmaCfg<T, 256, 128, 4, 2, 3, 64, true>::init();
-    MfmaCfg<T, 128, 128, 2, 2, 4>::init();
+    MfmaCfg<T, 128, 128, 4, 2, 4>::init();
     MfmaCfg<T, 128, 64, 2, 2, 4>::init();
     MfmaCfg<T, 128, 128, 2, 2, 2>::init();
     MfmaCfg<T, 128, 128, 2, 2, 3, 32>::init();
@@ -588,7 +588,7 @@ static int gemm_mfma_dispatch(const void *A, const void *W, void *C, int M, int 
     // the results are bit-identical)
     typedef MfmaCfg<T, 256, 128, 4, 2, 3, 64, true> CfgPrefill;
     typedef MfmaCfg<T, 256, 256, 4, 2, 4, 32, true> CfgWide;   // wave tile 64x128: three fragment reads per four products
-    typedef MfmaCfg<T, 128, 128, 2, 2, 4> CfgLarge;         // wave tile 64x64
+    typedef MfmaCfg<T, 128, 128, 4, 2, 4> CfgLarge;         // 8 waves of 32x64: up to 128 rows what counts is loads in flight (22 against 25 us for gate/up with 4 waves of 64x64)
     typedef MfmaCfg<T, 128, 128, 2, 2, 2> CfgLarge2;        // two stages, 64 KB of LDS: two blocks per CU
     typedef MfmaCfg<T, 128, 128, 2, 2, 3, 32> CfgLarge3;    // BK 32, 48 KB of LDS: three blocks per CU
     typedef MfmaCfg<T, 128, 64, 2, 2, 4> CfgMid;            // wave tile 64x32: long-K projections cut into K slices
