@@ -164,17 +164,7 @@ __global__ __launch_bounds__(64 * WM * WN) void gemm_mfma_kernel(const T *__rest
         // groups of 8, patch by patch of 4 row blocks x 8 column blocks.  The 32 blocks a die runs at a time then
         // share 4 activation slabs and 8 weight slabs (its L2 serves each K tile to 8 resp. 4 blocks), where plain
         // order gave a die 32 different weight slabs at once.
-        const int die = id % N_XCD, j = id / N_XCD;
-        const int rows_per = mb / N_XCD;
-        if (j >= rows_per * nb) return;
-        const int ph = (rows_per % 4 == 0) ? 4 : ((rows_per % 2 == 0) ? 2 : 1);
-        const int full = rows_per * 8;                        // tiles of a full group of 8 column blocks
-        const int cg = min(j / full, (nb - 1) / 8);
-        const int w = min(8, nb - 8 * cg);
-        const int jj = j - cg * full;
-        const int sg = jj / (ph * w), r = jj % (ph * w);
-        bm = die * rows_per + sg * ph + r % ph;
-        bn = 8 * cg + r / ph;
+        if (!gemm_patch_tile(id, mb, nb, &bm, &bn)) return;
         z = 0;
     } else if (plain) {   // many row blocks (prefill): neighbours share the activation rows, plain order
         bn = id % nb;

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "../../include/pc.h"
+#include "index_maps.h"
 
 namespace pc {
 
@@ -140,15 +141,10 @@ struct KvGeom {
     __host__ __device__ bool frag_major() const { return (head_dim & 31) == 0; }
     // element offsets of K[token tin][dim d] / V[token tin][dim d] inside one (block, kv head) region
     __host__ __device__ int k_index(int tin, int d) const {
-        if (!frag_major()) return tin * head_dim + d;
-        const int tt = tin & 31, u = (tt >> 2) & 1, i = ((tt >> 3) << 2) | (tt & 3);
-        const int frag = ((tin >> 5) * 2 + u) * (head_dim >> 5) + (d >> 5);
-        return (frag << 9) + (((((d & 31) >> 3) << 4) + i) << 3) + (d & 7);
+        return frag_major() ? kv_k_index_frag(tin, d, head_dim) : tin * head_dim + d;
     }
     __host__ __device__ int v_index(int tin, int d) const {
-        if (!frag_major()) return block_size * head_dim + d * block_size + tin;
-        const int frag = (tin >> 5) * (head_dim >> 4) + (d >> 4);
-        return block_size * head_dim + (frag << 9) + (((((tin & 31) >> 3) << 4) + (d & 15)) << 3) + (tin & 7);
+        return block_size * head_dim + (frag_major() ? kv_v_index_frag(tin, d, head_dim) : d * block_size + tin);
     }
 };
 

@@ -11,6 +11,7 @@
 #include <set>
 #include <vector>
 
+#include "../../paper_2605_26606_amd/csrc/index_maps.h"
 #include "../../paper_2605_26606_amd/csrc/kv_book.h"
 #include "../../paper_2605_26606_amd/csrc/scheduler.hip"
 
@@ -190,9 +191,81 @@ static int run_book(int n_ops) {
     return 0;
 }
 
+// The index maps of the kernels, checked exhaustively: the fragment-order cache layout is a bijection of a block's
+// (token, dim) pairs onto its elements in which every operand fragment is 512 consecutive elements with lane
+// (i, g) at element (16 g + i) * 8 holding what the matrix-core kernels expect there; the GEMM's patch order
+// visits every tile exactly once, gives every die the same number of tiles, and any 32 consecutive tiles of a die
+// touch at most 4 row blocks and 8 column blocks (ragged last column group aside).
+static int run_maps() {
+    using namespace pc;
+    for (int hd : {32, 64, 128, 256})
+        for (int bs : {32, 64, 128, 256}) {
+            std::vector<int> seen_k((size_t)bs * hd, 0), seen_v((size_t)bs * hd, 0);
+            for (int t = 0; t < bs; ++t)
+                for (int d = 0; d < hd; ++d) {
+                    const int k = kv_k_index_frag(t, d, hd), v = kv_v_index_frag(t, d, hd);
+                    REQUIRE(k >= 0 && k < bs * hd && v >= 0 && v < bs * hd);
+                    seen_k[k]++;
+                    seen_v[v]++;
+                }
+            for (int x : seen_k) REQUIRE(x == 1);
+            for (int x : seen_v) REQUIRE(x == 1);
+            // what lane (i, g) finds at its place in each fragment
+            for (int tile = 0; tile < bs / 32; ++tile)
+                for (int g = 0; g < 4; ++g)
+                    for (int i = 0; i < 16; ++i)
+                        for (int j = 0; j < 8; ++j) {
+                            for (int u = 0; u < 2; ++u)
+                                for (int kk = 0; kk < hd / 32; ++kk) {
+                                    const int tok = 32 * tile + 8 * (i / 4) + i % 4 + 4 * u, dim = 32 * kk + 8 * g + j;
+                                    REQUIRE(kv_k_index_frag(tok, dim, hd) ==
+                                            (((tile * 2 + u) * (hd / 32) + kk) << 9) + (16 * g + i) * 8 + j);
+                                }
+                            for (int nn = 0; nn < hd / 16; ++nn) {
+                                const int tok = 32 * tile + 8 * g + j, dim = 16 * nn + i;
+                                REQUIRE(kv_v_index_frag(tok, dim, hd) == ((tile * (hd / 16) + nn) << 9) + (16 * g + i) * 8 + j);
+                            }
+                        }
+        }
+    int checked = 0;
+    for (int mb : {8, 16, 24, 32, 40, 64, 128})
+        for (int nb : {1, 3, 6, 7, 8, 9, 12, 16, 70, 594, 1187}) {
+            std::vector<int> seen((size_t)mb * nb, 0);
+            std::vector<std::vector<std::pair<int, int>>> per_die(8);
+            int bm = -1, bn = -1;
+            for (int id = 0; id < mb * nb; ++id) {
+                REQUIRE(gemm_patch_tile(id, mb, nb, &bm, &bn));
+                REQUIRE(bm >= 0 && bm < mb && bn >= 0 && bn < nb);
+                seen[(size_t)bm * nb + bn]++;
+                per_die[id % 8].push_back({bm, bn});
+            }
+            REQUIRE(!gemm_patch_tile(mb * nb, mb, nb, &bm, &bn));
+            for (int x : seen) REQUIRE(x == 1);
+            const int ph = ((mb / 8) % 4 == 0) ? 4 : (((mb / 8) % 2 == 0) ? 2 : 1);
+            for (int die = 0; die < 8; ++die) {
+                REQUIRE((int)per_die[die].size() == mb / 8 * nb);
+                for (auto &t : per_die[die]) REQUIRE(t.first / (mb / 8) == die);   // a die keeps to its row blocks
+                // aligned windows of ph * 8 tiles inside full column groups are exactly one patch
+                const int full_groups = nb / 8, per_group = mb / 8 * 8;
+                for (int w0 = 0; w0 + ph * 8 <= full_groups * per_group; w0 += ph * 8) {
+                    std::set<int> rows, cols;
+                    for (int k = 0; k < ph * 8; ++k) {
+                        rows.insert(per_die[die][w0 + k].first);
+                        cols.insert(per_die[die][w0 + k].second);
+                    }
+                    REQUIRE((int)rows.size() == ph && (int)cols.size() == 8);
+                }
+            }
+            ++checked;
+        }
+    printf("maps ok: cache layouts for 16 geometries, %d tile grids\n", checked);
+    return 0;
+}
+
 int main(int argc, char **argv) {
+    if (argc > 1 && !strcmp(argv[1], "maps")) return run_maps();
     if (argc > 1 && !strcmp(argv[1], "sched")) return run_sched();
     if (argc > 2 && !strcmp(argv[1], "book")) return run_book(atoi(argv[2]));
-    fprintf(stderr, "usage: host_checks sched < trace | host_checks book N\n");
+    fprintf(stderr, "usage: host_checks sched < trace | host_checks book N | host_checks maps\n");
     return 2;
 }

@@ -1,6 +1,7 @@
-"""The library's host-side C++ (the multi-step scheduler and the KV-cache
-bookkeeping: real sources, no copies) built for the CPU with the address and
-undefined-behaviour sanitizers and driven without a GPU:
+"""The library's host-side C++ (the multi-step scheduler, the KV-cache
+bookkeeping and the kernels' index maps: real sources, no copies) built for
+the CPU with the address and undefined-behaviour sanitizers and driven without
+a GPU:
 
   * the scheduler replays a synthetic multi-epoch training run (drifting
     success rates, second sampling rounds, age-outs, evictions) and every
@@ -43,6 +44,13 @@ def _run(exe, args, stdin=""):
     assert p.returncode == 0, "exit %d\n%s\n%s" % (p.returncode, p.stdout[-2000:], p.stderr[-4000:])
     assert "ERROR: AddressSanitizer" not in p.stderr and "runtime error" not in p.stderr, p.stderr[-4000:]
     return p.stdout
+
+
+def test_index_maps_exhaustively(host_checks):
+    """The kernels' index arithmetic (csrc/index_maps.h, the same header the kernels include): the operand-fragment
+    cache layout and the GEMM's tile order, checked over every geometry the library accepts."""
+    out = _run(host_checks, ["maps"])
+    assert out.startswith("maps ok")
 
 
 def test_kv_bookkeeping_under_sanitizers(host_checks):
