@@ -120,7 +120,6 @@ static constexpr int N_XCD = 8;   // MI355X: 8 accelerator dies, each with its o
 // 64 k); to keep the 128-bit fragment reads conflict free without padding, the 16-byte chunk c of
 // row r is stored at chunk slot c ^ swz(r) (the lane fetches the chunk its slot must hold), where swz
 // makes any 16 consecutive rows hit 16 different 16-byte bank groups.  K must be a multiple of 64 here.
-__device__ inline void wait_vmcnt(int) {}
 template <int N> __device__ inline void wait_vmcnt_le() {
     // s_waitcnt with only the vector-memory counter set (gfx9 encoding: vmcnt = bits 15:14 | 3:0)
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
