@@ -432,9 +432,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    if not args.no_parity and eos_id < 0 and m.dtype == "bf16":
+    if not args.no_parity and m.dtype == "bf16":   # (its own pilot pass, generated without an EOS id)
         result["parity"] = parity_sample(pc, ctx, wl, w, toks, cu, prompts, uids, wl.seed_sampler + 5, stream,
-                                         span=args.parity_span, say=say if m.n_layers * m.d_model > 28 * 1536 else None)
+                                         span=args.parity_span,
+                                         say=say if m.n_layers * m.d_model * (Lp + T) > 28 * 1536 * 1500 else None)
         say("parity sample done")
     result["saturated_stores"] = pc.pc_saturation_count(ctx)
     if not args.no_cpu_baseline:
