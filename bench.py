@@ -128,7 +128,7 @@ def parity_sample(pc, ctx, wl, w_dev, toks, cu, prompts, uids, seed, stream, spa
         handles = pc.pc_prefill_shared(ctx, toks, cu, last, stream)
         rows = np.repeat(np.arange(P, dtype=np.int32), wl.n_pilot)
         seq_uids = (np.asarray(uids, np.int64)[:, None] * 65536 + np.arange(wl.n_pilot)[None, :]).reshape(-1)
-        g = pc.generate(ctx, handles[rows], rows, last, seq_uids, T, wl.temperature, seed, -1, 0.0, stream,
+        g = pc.generate(ctx, handles[rows], rows, last, seq_uids, Ts, wl.temperature, seed, -1, 0.0, stream,
                         keep_logits_rows=np.array([seq]), keep_logits_steps=steps)
         pc.pc_release(ctx, handles, 1)
     torch.cuda.synchronize()
